@@ -1,0 +1,97 @@
+"""Pins for the oracle's load metrics, partitioner and re-pack (CPU only)."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import dynmo_oracle as orc
+
+
+def read_golden(path):
+    rows = []
+    with open(path) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                rows.append([c.strip() for c in line.split("|")])
+    return rows
+
+
+def brute_bottleneck(loads, S):
+    """Enumerate every contiguous split into S non-empty stages."""
+    L = len(loads)
+    best = None
+    for cuts in itertools.combinations(range(1, L), S - 1):
+        b = (0,) + cuts + (L,)
+        m = max(sum(loads[b[i]:b[i + 1]]) for i in range(S))
+        best = m if best is None else min(best, m)
+    return best
+
+
+def test_imbalance_hand_values(golden_dir):
+    for exp, loads in read_golden(os.path.join(golden_dir, "imbalance_hand.txt")):
+        L = [float(v) for v in loads.split()]
+        assert orc.imbalance(L) == pytest.approx(float(exp), rel=1e-15, abs=1e-15)
+
+
+def test_partition_hand_values(golden_dir):
+    for S, bott, bounds, loads in read_golden(os.path.join(golden_dir, "partition_hand.txt")):
+        S = int(S)
+        L = [float(v) for v in loads.split()]
+        b = orc.partition_dp(L, S)
+        assert b == float(bott)
+        cb = orc.partition_canonical_bounds(L, S, b)
+        assert list(cb) == [int(v) for v in bounds.split()]
+        assert orc.stage_loads(L, cb).max() == b
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_partition_dp_equals_enumeration(seed):
+    rng = np.random.default_rng(seed)
+    for _ in range(10):
+        L = int(rng.integers(1, 12))
+        S = int(rng.integers(1, L + 1))
+        loads = [float(v) for v in rng.integers(0, 50, size=L)]  # integer-valued: sums are exact
+        b = orc.partition_dp(loads, S)
+        assert b == brute_bottleneck(loads, S)
+        cb = orc.partition_canonical_bounds(loads, S, b)
+        assert cb[0] == 0 and cb[-1] == L and all(cb[i] < cb[i + 1] for i in range(S))
+        assert orc.stage_loads(loads, cb).max() == b
+
+
+def test_partition_special_cases():
+    assert orc.partition_dp([3.0] * 12, 4) == 9.0
+    assert list(orc.partition_canonical_bounds([3.0] * 12, 4, 9.0)) == [0, 3, 6, 9, 12]
+    assert orc.partition_dp([1, 1, 50, 1, 1], 5) == 50.0
+    assert list(orc.uniform_bounds(10, 4)) == [0, 3, 6, 8, 10]
+    # balancing never does worse than the static equal-count split
+    rng = np.random.default_rng(1)
+    loads = np.sort(rng.integers(1, 100, size=24))[::-1].astype(float)  # early-exit-like decay
+    ub = orc.stage_loads(loads, orc.uniform_bounds(24, 6))
+    b = orc.partition_dp(loads, 6)
+    pb = orc.stage_loads(loads, orc.partition_canonical_bounds(loads, 6, b))
+    assert pb.max() <= ub.max()
+    assert pb.max() == b
+    # fewer layers than stages: trailing stages are empty
+    assert orc.partition_dp([5.0, 7.0], 4) == 7.0
+
+
+def test_repack_hand_trace():
+    """Algorithm 2 traced by hand on four workers, MAX_MEM = 10.
+    mem = [3,4,2,6], layers = [2,3,1,2], target 2.
+    (0,1): 3+4<10, 4>2 -> merge 0 into 1: mem1=7, layers1=5, active=3.
+    (1,2): 7+2<10, 3>2 -> merge 1 into 2: mem2=9, layers2=6, active=2.
+    (2,3): active == target -> stop."""
+    tr, act, mem, nl = orc.repack_first_fit([1, 1, 1, 1], [3, 4, 2, 6], [2, 3, 1, 2], 2, 10)
+    assert tr == [(0, 1, 0), (0, 1, 1)] + [(1, 2, i) for i in range(5)]
+    assert act == [0, 0, 1, 1] and mem[2] == 9 and nl[2] == 6
+    # memory bound blocks every merge
+    tr, act, _, _ = orc.repack_first_fit([1, 1, 1], [6, 6, 6], [1, 1, 1], 1, 10)
+    assert tr == [] and act == [1, 1, 1]
+    # already at the target
+    tr, act, _, _ = orc.repack_first_fit([1, 1], [1, 1], [4, 4], 2, 10)
+    assert tr == []
+    # first fit skips a partner that does not fit and takes the next one
+    tr, act, mem, nl = orc.repack_first_fit([1, 1, 1], [5, 6, 2], [1, 1, 1], 2, 10)
+    assert tr == [(0, 2, 0)] and act == [0, 1, 1] and mem[2] == 7
