@@ -1,0 +1,188 @@
+/*
+ * dynmo.h -- C ABI of the MI355X (gfx950) token-routed sparse FFN layer.
+ *
+ * The layer is the unit of work whose cost DynMo (arXiv 2505.14864) profiles and
+ * rebalances: tokens are routed to experts (Sec. 2.1), or bypass the layer
+ * (Mixture-of-Depths, Sec. 2.6), or have left the network early (Sec. 2.5), and
+ * the work of the layer is the per-token FFN cost times the routed-token count.
+ *
+ * Conventions for every call
+ *   - returns DYNMO_OK (0) or a negative DYNMO_E* code; never throws or aborts.
+ *   - every tensor pointer is a DEVICE pointer owned by the caller unless the
+ *     parameter name ends in _host.  The library keeps no device memory: scratch
+ *     comes from the caller's workspace (size from dynmo_*_workspace_bytes).
+ *   - outputs are overwritten, never accumulated into.
+ *   - `stream` is a hipStream_t (NULL = the default stream).  Calls enqueue work
+ *     and return; only dynmo_layer_load synchronises the stream.
+ *   - tensors are row-major and contiguous.  T tokens, H hidden size, F FFN size,
+ *     E experts, k slots per token; flat slot i = t*k + s.  Index type int32,
+ *     -1 = "slot not routed".  R = number of routed slots = seg_offsets[E].
+ *     Buffers with a leading R dimension are sized for the worst case T*k; rows
+ *     at or beyond R are left unspecified.
+ *   - dtype DYNMO_F32: activations/weights float.  DYNMO_BF16: bfloat16 storage,
+ *     fp32 accumulation, results rounded to nearest-even once.
+ *     Logits, scores, gate weights and their gradients are always float.
+ *   - weights: Wg, Wu are [E, F, H]; Wd is [E, H, F].
+ *   - limits: 1 <= k <= E <= 64 (k <= 8 for the combine calls); for DYNMO_BF16
+ *     H and F must be multiples of 8.  Violations return DYNMO_EINVAL /
+ *     DYNMO_EUNSUPPORTED before anything is launched.
+ *   - NaN in logits or scores is undefined input.
+ */
+#ifndef DYNMO_H
+#define DYNMO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  DYNMO_OK = 0,
+  DYNMO_EINVAL = -1,       /* null pointer, bad shape, k > E, cap > S ... */
+  DYNMO_EUNSUPPORTED = -2, /* shape or dtype outside the limits above */
+  DYNMO_EWORKSPACE = -3,   /* workspace smaller than the *_workspace_bytes value */
+  DYNMO_EHIP = -4          /* a HIP call failed; see dynmo_last_hip_error() */
+};
+
+enum { DYNMO_F32 = 0, DYNMO_BF16 = 1 };
+
+typedef struct dynmo_desc {
+  int32_t T;     /* tokens */
+  int32_t H;     /* hidden size */
+  int32_t F;     /* FFN intermediate size */
+  int32_t E;     /* experts (1 for Mixture-of-Depths / early exit) */
+  int32_t k;     /* slots per token (1 for Mixture-of-Depths / early exit) */
+  int32_t dtype; /* DYNMO_F32 or DYNMO_BF16 */
+} dynmo_desc;
+
+int32_t dynmo_version(void);
+/* The hipError_t of the last failed HIP call made by this library on the calling thread. */
+int32_t dynmo_last_hip_error(void);
+
+/* ---- route ------------------------------------------------------------- */
+
+/* Token-choice top-k routing, the routing function R of Sec. 2.1.  Per token the
+ * experts are ordered by (logit descending, expert index ascending); slot s gets
+ * the s-th of them; gate_w is the softmax over the k selected logits.
+ * logits [T,E] -> expert_idx [T,k], gate_w [T,k]. */
+int32_t dynmo_route_topk(const dynmo_desc* d, const float* logits, int32_t* expert_idx, float* gate_w,
+                         void* stream);
+
+/* Mixture-of-Depths capacity routing (Sec. 2.6): per sequence of S scores the
+ * `cap` largest (ties: lower position) are processed, the rest bypass the layer.
+ * Needs T == B*S, E == 1, k == 1, 0 <= cap <= S.
+ * scores [B,S] -> expert_idx [T,1] (0 selected / -1 not), gate_w [T,1]
+ * (sigmoid(score) if selected, else 0). */
+int32_t dynmo_route_capacity(const dynmo_desc* d, const float* scores, int32_t B, int32_t S, int32_t cap,
+                             int32_t* expert_idx, float* gate_w, void* stream);
+
+/* Early-exit activity (Sec. 2.5): a token is processed by stage-local layer
+ * `layer` (1-based) iff exit_layer[t] >= layer.  Needs E == 1, k == 1.
+ * exit_layer [T] -> expert_idx [T,1] (0 / -1), gate_w [T,1] (1 / 0). */
+int32_t dynmo_route_active(const dynmo_desc* d, const int32_t* exit_layer, int32_t layer, int32_t* expert_idx,
+                           float* gate_w, void* stream);
+
+/* Backward of dynmo_route_topk through the gate softmax (the selection carries no
+ * gradient): dlogits[t,e_s] = w_s (dgate_s - sum_j w_j dgate_j), zero elsewhere.
+ * dgate [T,k], gate_w [T,k], expert_idx [T,k] -> dlogits [T,E]. */
+int32_t dynmo_route_topk_bwd(const dynmo_desc* d, const float* dgate, const float* gate_w,
+                             const int32_t* expert_idx, float* dlogits, void* stream);
+
+/* Backward of dynmo_route_capacity: dscores[t] = sigmoid'(score) dgate[t] for
+ * selected tokens, zero otherwise.  All arrays [T]. */
+int32_t dynmo_route_capacity_bwd(const dynmo_desc* d, const float* dgate, const float* scores,
+                                 const int32_t* expert_idx, float* dscores, void* stream);
+
+/* ---- permute ----------------------------------------------------------- */
+
+size_t dynmo_permute_workspace_bytes(const dynmo_desc* d);
+
+/* Groups the routed slots into one contiguous row segment per expert -- the
+ * token sets R^-1(e) of Sec. 2.1 -- by a stable counting sort of the flat slots
+ * keyed by expert: row p = seg_offsets[e] + (number of earlier slots of expert e).
+ * x [T,H], expert_idx [T,k] -> x_p [T*k,H] (x_p[p] = x[src_slot[p] / k]),
+ * seg_offsets [E+1], src_slot [T*k], dst_pos [T,k] (-1 if unrouted).
+ * The result is deterministic (no dependence on atomic ordering). */
+int32_t dynmo_permute(const dynmo_desc* d, const void* x, const int32_t* expert_idx, void* x_p,
+                      int32_t* seg_offsets, int32_t* src_slot, int32_t* dst_pos, void* workspace,
+                      size_t workspace_bytes, void* stream);
+
+/* Backward of permute (and of the pass-through residual when dbase != NULL):
+ * dx[t] = dbase[t] + sum over routed slots s of dx_p[dst_pos[t,s]].
+ * dx_p [T*k,H], dst_pos [T,k], dbase [T,H] or NULL -> dx [T,H]. */
+int32_t dynmo_permute_bwd(const dynmo_desc* d, const void* dx_p, const int32_t* dst_pos, const void* dbase,
+                          void* dx, void* stream);
+
+/* ---- grouped FFN ------------------------------------------------------- */
+
+size_t dynmo_grouped_ffn_fwd_workspace_bytes(const dynmo_desc* d);
+
+/* The per-token workload c_e of Sec. 2.1 (c_i of Sec. 2.5 / 2.6): for the rows of
+ * each expert segment, G = X Wg[e]^T, U = X Wu[e]^T, A = silu(G) * U, Y = A Wd[e]^T.
+ * x_p [T*k,H], seg_offsets [E+1], weights -> y_p [T*k,H]; G_save, U_save [T*k,F]
+ * are kept for the backward pass. */
+int32_t dynmo_grouped_ffn_fwd(const dynmo_desc* d, const void* x_p, const int32_t* seg_offsets, const void* Wg,
+                              const void* Wu, const void* Wd, void* y_p, void* G_save, void* U_save,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+size_t dynmo_grouped_ffn_bwd_workspace_bytes(const dynmo_desc* d);
+
+/* Backward of dynmo_grouped_ffn_fwd: dA = dY Wd; dG = dA U silu'(G); dU = dA silu(G);
+ * dWd[e] = dY_e^T A_e; dX = dG Wg + dU Wu; dWg[e] = dG_e^T X_e; dWu[e] = dU_e^T X_e.
+ * dWg, dWu [E,F,H] and dWd [E,H,F] are fully overwritten (zeros for an expert
+ * with no rows); dx_p [T*k,H]. */
+int32_t dynmo_grouped_ffn_bwd(const dynmo_desc* d, const void* dy_p, const void* x_p, const void* G_save,
+                              const void* U_save, const int32_t* seg_offsets, const void* Wg, const void* Wu,
+                              const void* Wd, void* dx_p, void* dWg, void* dWu, void* dWd, void* workspace,
+                              size_t workspace_bytes, void* stream);
+
+/* ---- combine ----------------------------------------------------------- */
+
+/* out[t] = base[t] + sum over routed slots s (ascending) of gate_w[t,s] y_p[dst_pos[t,s]].
+ * base is NULL (zero) for MoE and the layer input for Mixture-of-Depths / early
+ * exit, whose unrouted tokens pass through unchanged (Sec. 2.5, 2.6).  out must
+ * not alias base.  y_p [T*k,H], dst_pos [T,k], gate_w [T,k] -> out [T,H]. */
+int32_t dynmo_combine(const dynmo_desc* d, const void* y_p, const int32_t* dst_pos, const float* gate_w,
+                      const void* base, void* out, void* stream);
+
+/* Backward of combine: dy_p[p] = gate_w[t,s] dout[t]; dgate[t,s] = <dout[t], y_p[p]>
+ * with p = dst_pos[t,s] (dgate = 0 for unrouted slots). */
+int32_t dynmo_combine_bwd(const dynmo_desc* d, const void* dout, const void* y_p, const int32_t* dst_pos,
+                          const float* gate_w, void* dy_p, float* dgate, void* stream);
+
+/* ---- load export and the host-side balancer ---------------------------- */
+
+/* Exports the load the balancer consumes (Sec. 2.1: tokens per expert times the
+ * per-token cost; Sec. 2.5 / 2.6 with one expert).  Copies seg_offsets to the
+ * host, synchronises `stream`, and writes counts_host[e] = rows of expert e and
+ * *load_host = sum_e counts[e] * cost_per_row.  counts_host [E] and load_host
+ * are HOST pointers. */
+int32_t dynmo_layer_load(const dynmo_desc* d, const int32_t* seg_offsets, double cost_per_row,
+                         int32_t* counts_host, double* load_host, void* stream);
+
+/* Partition balancer (Sec. 3.3, Sec. 5: contiguous layers to stages, "binary
+ * search and linear probing"): the contiguous split of loads[L] into S stages
+ * that minimises the largest stage load (the min-max objective of Sec. 2).
+ * Writes bounds_host[S+1] (stage i owns layers bounds[i] .. bounds[i+1]-1): the
+ * split where each stage takes as many layers as fit under the optimal
+ * bottleneck while leaving one layer for each later stage; *bottleneck_host gets
+ * the optimum.  Host pointers only; loads must be finite and >= 0. */
+int32_t dynmo_partition(const double* loads_host, int32_t L, int32_t S, int32_t* bounds_host,
+                        double* bottleneck_host);
+
+/* Equal layer counts per stage (the static split the paper compares against). */
+int32_t dynmo_uniform_bounds(int32_t L, int32_t S, int32_t* bounds_host);
+
+/* Stage loads L_i of Sec. 2 for a contiguous assignment. */
+int32_t dynmo_stage_loads(const double* loads_host, int32_t L, const int32_t* bounds_host, int32_t S,
+                          double* stage_loads_host);
+
+/* Imbalance (L_max - L_min) / mean(L) of Sec. 2, Eq. 1-2. */
+int32_t dynmo_imbalance(const double* stage_loads_host, int32_t S, double* imbalance_host);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DYNMO_H */

@@ -1,0 +1,57 @@
+// C-ABI entry points of the grouped SwiGLU FFN: argument checks, workspace
+// carving and the choice of kernel family.
+#include "ffn.h"
+
+using namespace dynmo;
+
+namespace dynmo {
+thread_local int32_t g_last_hip_error = 0;
+
+static size_t act_bytes(const dynmo_desc* d) {  // one [T*k, F] activation buffer
+  return align_up((size_t)d->T * d->k * d->F * elem_bytes(d->dtype), 256);
+}
+}  // namespace dynmo
+
+extern "C" int32_t dynmo_version(void) { return 1; }
+extern "C" int32_t dynmo_last_hip_error(void) { return g_last_hip_error; }
+
+extern "C" size_t dynmo_grouped_ffn_fwd_workspace_bytes(const dynmo_desc* d) {
+  if (check_desc(d)) return 0;
+  return act_bytes(d) + 256;  // A = silu(G) U
+}
+
+extern "C" size_t dynmo_grouped_ffn_bwd_workspace_bytes(const dynmo_desc* d) {
+  if (check_desc(d)) return 0;
+  return 3 * act_bytes(d) + 256;  // dG, dU, A
+}
+
+extern "C" int32_t dynmo_grouped_ffn_fwd(const dynmo_desc* d, const void* x_p, const int32_t* seg_offsets,
+                                         const void* Wg, const void* Wu, const void* Wd, void* y_p, void* G_save,
+                                         void* U_save, void* workspace, size_t workspace_bytes, void* stream) {
+  int32_t rc = check_desc(d);
+  if (rc) return rc;
+  if (!x_p || !seg_offsets || !Wg || !Wu || !Wd || !y_p || !G_save || !U_save || !workspace) return DYNMO_EINVAL;
+  if (workspace_bytes < dynmo_grouped_ffn_fwd_workspace_bytes(d)) return DYNMO_EWORKSPACE;
+  if (max_m_tiles(d, 64) > 65535) return DYNMO_EUNSUPPORTED;
+  void* A = (void*)align_up((size_t)workspace, 256);
+  return ffn_fwd_generic(d, x_p, seg_offsets, Wg, Wu, Wd, y_p, G_save, U_save, A, (hipStream_t)stream);
+}
+
+extern "C" int32_t dynmo_grouped_ffn_bwd(const dynmo_desc* d, const void* dy_p, const void* x_p, const void* G_save,
+                                         const void* U_save, const int32_t* seg_offsets, const void* Wg,
+                                         const void* Wu, const void* Wd, void* dx_p, void* dWg, void* dWu, void* dWd,
+                                         void* workspace, size_t workspace_bytes, void* stream) {
+  int32_t rc = check_desc(d);
+  if (rc) return rc;
+  if (!dy_p || !x_p || !G_save || !U_save || !seg_offsets || !Wg || !Wu || !Wd || !dx_p || !dWg || !dWu || !dWd ||
+      !workspace)
+    return DYNMO_EINVAL;
+  if (workspace_bytes < dynmo_grouped_ffn_bwd_workspace_bytes(d)) return DYNMO_EWORKSPACE;
+  if (max_m_tiles(d, 64) > 65535) return DYNMO_EUNSUPPORTED;
+  char* base = (char*)align_up((size_t)workspace, 256);
+  void* dG = base;
+  void* dU = base + act_bytes(d);
+  void* A = base + 2 * act_bytes(d);
+  return ffn_bwd_generic(d, dy_p, x_p, G_save, U_save, seg_offsets, Wg, Wu, Wd, dx_p, dWg, dWu, dWd, dG, dU, A,
+                         (hipStream_t)stream);
+}

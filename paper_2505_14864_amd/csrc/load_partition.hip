@@ -1,0 +1,140 @@
+// Load export (device -> host) and the host-side Partition balancer.
+#include <math.h>
+
+#include <vector>
+
+#include "common.h"
+
+using namespace dynmo;
+
+extern "C" int32_t dynmo_layer_load(const dynmo_desc* d, const int32_t* seg_offsets, double cost_per_row,
+                                    int32_t* counts_host, double* load_host, void* stream) {
+  int32_t rc = check_desc(d);
+  if (rc) return rc;
+  if (!seg_offsets || !counts_host || !load_host) return DYNMO_EINVAL;
+  int32_t seg[kMaxExperts + 1];
+  hipStream_t st = (hipStream_t)stream;
+  DYNMO_HIP_TRY(hipMemcpyAsync(seg, seg_offsets, sizeof(int32_t) * (d->E + 1), hipMemcpyDeviceToHost, st));
+  DYNMO_HIP_TRY(hipStreamSynchronize(st));
+  double rows = 0.0;
+  for (int e = 0; e < d->E; ++e) {
+    counts_host[e] = seg[e + 1] - seg[e];
+    rows += (double)counts_host[e];
+  }
+  *load_host = rows * cost_per_row;
+  return DYNMO_OK;
+}
+
+namespace {
+
+// Stage sums are differences of one running prefix sum, so that every candidate
+// bottleneck is a value of the form prefix[j] - prefix[i].
+struct Prefix {
+  std::vector<double> p;
+  Prefix(const double* loads, int L) : p((size_t)L + 1, 0.0) {
+    for (int i = 0; i < L; ++i) p[i + 1] = p[i] + loads[i];
+  }
+  double sum(int i, int j) const { return p[j] - p[i]; }
+};
+
+// Linear probe: can the layers be covered by at most S contiguous stages whose
+// sums do not exceed `cap`?  Greedy left to right.
+bool feasible(const Prefix& pre, int L, int S, double cap) {
+  int start = 0, used = 0;
+  while (start < L) {
+    if (used == S) return false;
+    int end = start;
+    while (end < L && pre.sum(start, end + 1) <= cap) ++end;
+    if (end == start) return false;  // a single layer exceeds cap
+    start = end;
+    ++used;
+  }
+  return true;
+}
+
+}  // namespace
+
+extern "C" int32_t dynmo_partition(const double* loads_host, int32_t L, int32_t S, int32_t* bounds_host,
+                                   double* bottleneck_host) {
+  if (!loads_host || !bounds_host || !bottleneck_host || L < 0 || S <= 0) return DYNMO_EINVAL;
+  for (int i = 0; i < L; ++i)
+    if (!(loads_host[i] >= 0.0) || !isfinite(loads_host[i])) return DYNMO_EINVAL;
+  Prefix pre(loads_host, L);
+  // Binary search on the bottleneck value.  Feasibility is monotone in the cap,
+  // and the optimum is itself a double (some prefix difference), so bisecting
+  // down to adjacent doubles lands exactly on it.
+  double lo = 0.0;  // lo is infeasible unless it is the answer
+  for (int i = 0; i < L; ++i) lo = fmax(lo, loads_host[i]);
+  double hi = pre.sum(0, L);
+  if (hi < lo) hi = lo;
+  double best = hi;
+  if (L == 0 || feasible(pre, L, S, lo)) {
+    best = lo;
+  } else {
+    while (true) {
+      const double mid = lo + (hi - lo) * 0.5;
+      if (!(mid > lo) || !(mid < hi)) break;
+      if (feasible(pre, L, S, mid))
+        hi = mid;
+      else
+        lo = mid;
+    }
+    best = hi;
+  }
+  // The split: each stage takes as many layers as fit, but leaves one layer for
+  // every later stage (when there are at least as many layers as stages).
+  int start = 0;
+  bounds_host[0] = 0;
+  double realised = 0.0;
+  for (int s = 0; s < S; ++s) {
+    int end;
+    if (s == S - 1) {
+      end = L;
+    } else {
+      const int limit = L >= S ? L - (S - s - 1) : L;
+      end = start;
+      while (end < limit && pre.sum(start, end + 1) <= best) ++end;
+      if (L >= S && end == start) end = start + 1;
+    }
+    realised = fmax(realised, pre.sum(start, end));
+    bounds_host[s + 1] = end;
+    start = end;
+  }
+  *bottleneck_host = realised;
+  return DYNMO_OK;
+}
+
+extern "C" int32_t dynmo_uniform_bounds(int32_t L, int32_t S, int32_t* bounds_host) {
+  if (!bounds_host || L < 0 || S <= 0) return DYNMO_EINVAL;
+  const int base = L / S, rem = L % S;
+  bounds_host[0] = 0;
+  for (int s = 0; s < S; ++s) bounds_host[s + 1] = bounds_host[s] + base + (s < rem ? 1 : 0);
+  return DYNMO_OK;
+}
+
+extern "C" int32_t dynmo_stage_loads(const double* loads_host, int32_t L, const int32_t* bounds_host, int32_t S,
+                                     double* stage_loads_host) {
+  if (!loads_host || !bounds_host || !stage_loads_host || L < 0 || S <= 0) return DYNMO_EINVAL;
+  if (bounds_host[0] != 0 || bounds_host[S] != L) return DYNMO_EINVAL;
+  for (int s = 0; s < S; ++s)
+    if (bounds_host[s] > bounds_host[s + 1]) return DYNMO_EINVAL;
+  for (int s = 0; s < S; ++s) {
+    double acc = 0.0;
+    for (int i = bounds_host[s]; i < bounds_host[s + 1]; ++i) acc += loads_host[i];
+    stage_loads_host[s] = acc;
+  }
+  return DYNMO_OK;
+}
+
+extern "C" int32_t dynmo_imbalance(const double* stage_loads_host, int32_t S, double* imbalance_host) {
+  if (!stage_loads_host || !imbalance_host || S <= 0) return DYNMO_EINVAL;
+  double mx = stage_loads_host[0], mn = stage_loads_host[0], sum = 0.0;
+  for (int s = 0; s < S; ++s) {
+    mx = fmax(mx, stage_loads_host[s]);
+    mn = fmin(mn, stage_loads_host[s]);
+    sum += stage_loads_host[s];
+  }
+  if (!(sum > 0.0)) return DYNMO_EINVAL;
+  *imbalance_host = (mx - mn) / (sum / S);
+  return DYNMO_OK;
+}

@@ -1,0 +1,244 @@
+// Permutation of routed token rows into contiguous per-expert segments, and its
+// backward.  The index part is a stable counting sort done without ordered
+// atomics: per-chunk histograms, a scan over chunks, then an in-chunk stable rank
+// from wavefront ballots.  The row movement is a token-centric copy: each source
+// row is read once and written to its (up to k) destinations with 16-byte
+// accesses.
+#include "common.h"
+
+namespace dynmo {
+
+constexpr int kChunkThreads = 256;
+constexpr int kChunkPasses = 4;
+constexpr int kChunk = kChunkThreads * kChunkPasses;  // slots per workgroup
+
+// chunk_counts[c*E + e] = number of slots of expert e in chunk c
+__global__ __launch_bounds__(kChunkThreads) void permute_count_kernel(const int32_t* __restrict__ expert_idx, int n_slots,
+                                                                      int E, int32_t* __restrict__ chunk_counts) {
+  __shared__ int cnt[kMaxExperts];
+  if (threadIdx.x < E) cnt[threadIdx.x] = 0;
+  __syncthreads();
+  const int base = blockIdx.x * kChunk;
+#pragma unroll
+  for (int p = 0; p < kChunkPasses; ++p) {
+    const int i = base + p * kChunkThreads + threadIdx.x;
+    if (i < n_slots) {
+      const int e = expert_idx[i];
+      if (e >= 0 && e < E) atomicAdd(&cnt[e], 1);  // integer sum: order-independent
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < E) chunk_counts[blockIdx.x * E + threadIdx.x] = cnt[threadIdx.x];
+}
+
+// One workgroup.  Turns chunk_counts into chunk bases (in place) and writes
+// seg_offsets[E+1].  Thread e walks the chunks of expert e.
+__global__ __launch_bounds__(2 * kMaxExperts) void permute_scan_kernel(int32_t* __restrict__ chunk_counts, int n_chunks, int E,
+                                                                   int32_t* __restrict__ seg_offsets) {
+  __shared__ int total[kMaxExperts];
+  __shared__ int seg[kMaxExperts + 1];
+  const int e = threadIdx.x;
+  if (e < E) {
+    int s = 0;
+    for (int c = 0; c < n_chunks; ++c) s += chunk_counts[c * E + e];
+    total[e] = s;
+  }
+  __syncthreads();
+  if (e == 0) {
+    int run = 0;
+    for (int j = 0; j < E; ++j) {
+      seg[j] = run;
+      run += total[j];
+    }
+    seg[E] = run;
+  }
+  __syncthreads();
+  if (e <= E) seg_offsets[e] = seg[e];
+  if (e < E) {
+    int run = seg[e];
+    for (int c = 0; c < n_chunks; ++c) {
+      const int v = chunk_counts[c * E + e];
+      chunk_counts[c * E + e] = run;
+      run += v;
+    }
+  }
+}
+
+// Stable rank of every slot inside its chunk, added to the chunk base.
+__global__ __launch_bounds__(kChunkThreads) void permute_scatter_kernel(const int32_t* __restrict__ expert_idx,
+                                                                        int n_slots, int E,
+                                                                        const int32_t* __restrict__ chunk_base,
+                                                                        int32_t* __restrict__ src_slot,
+                                                                        int32_t* __restrict__ dst_pos) {
+  constexpr int kWaves = kChunkThreads / 64;
+  __shared__ int run[kMaxExperts];             // rows of expert e already placed by earlier passes
+  __shared__ int wave_cnt[kWaves][kMaxExperts];
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  if (threadIdx.x < E) run[threadIdx.x] = chunk_base[blockIdx.x * E + threadIdx.x];
+  __syncthreads();
+  const int base = blockIdx.x * kChunk;
+  for (int p = 0; p < kChunkPasses; ++p) {
+    const int i = base + p * kChunkThreads + threadIdx.x;
+    int e = -1;
+    if (i < n_slots) {
+      e = expert_idx[i];
+      if (e >= E) e = -1;
+    }
+    // rank among lower lanes of this wavefront with the same expert
+    int rank = 0;
+    for (int q = 0; q < E; ++q) {
+      const unsigned long long m = __ballot(e == q);
+      if (e == q) rank = __popcll(m & ((1ull << lane) - 1ull));
+      if (lane == q) wave_cnt[wv][q] = __popcll(m);
+    }
+    __syncthreads();
+    if (e >= 0) {
+      int pos = run[e] + rank;
+      for (int w = 0; w < wv; ++w) pos += wave_cnt[w][e];
+      dst_pos[i] = pos;
+      src_slot[pos] = i;
+    } else if (i < n_slots) {
+      dst_pos[i] = -1;
+    }
+    __syncthreads();
+    if (threadIdx.x < E) {
+      int s = 0;
+      for (int w = 0; w < kWaves; ++w) s += wave_cnt[w][threadIdx.x];
+      run[threadIdx.x] += s;
+    }
+    __syncthreads();
+  }
+}
+
+// One wavefront per token: read the row once, write it to each routed slot.
+template <int MAXK>
+__global__ __launch_bounds__(256) void permute_rows_kernel(const u32x4* __restrict__ x, const int32_t* __restrict__ dst_pos,
+                                                           u32x4* __restrict__ x_p, int T, int k, int row_vecs) {
+  const int lane = threadIdx.x & 63;
+  const long t = ((long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  if (t >= T) return;
+  long dst[MAXK];
+  bool any = false;
+#pragma unroll
+  for (int s = 0; s < MAXK; ++s) {
+    dst[s] = -1;
+    if (s < k) {
+      const int p = dst_pos[t * k + s];
+      if (p >= 0) {
+        dst[s] = (long)p * row_vecs;
+        any = true;
+      }
+    }
+  }
+  if (!any) return;
+  const u32x4* src = x + t * row_vecs;
+  for (int c = lane; c < row_vecs; c += 64 * 4) {
+    u32x4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (c + u * 64 < row_vecs) v[u] = src[c + u * 64];
+#pragma unroll
+    for (int s = 0; s < MAXK; ++s) {
+      if (dst[s] >= 0) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (c + u * 64 < row_vecs) x_p[dst[s] + c + u * 64] = v[u];
+      }
+    }
+  }
+}
+
+// dx[t] = dbase[t] + sum_s dx_p[dst_pos[t,s]]  (fp32 sum in ascending s)
+template <typename T>
+__global__ __launch_bounds__(256) void permute_bwd_kernel(const u32x4* __restrict__ dx_p, const int32_t* __restrict__ dst_pos,
+                                                          const u32x4* __restrict__ dbase, u32x4* __restrict__ dx, int Tn,
+                                                          int k, int row_vecs) {
+  constexpr int V = Elem<T>::kVec;
+  const int lane = threadIdx.x & 63;
+  const long t = ((long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  if (t >= Tn) return;
+  for (int c = lane; c < row_vecs; c += 64) {
+    float acc[V];
+    if (dbase) {
+      unpack16<T>(dbase[t * row_vecs + c], acc);
+    } else {
+#pragma unroll
+      for (int j = 0; j < V; ++j) acc[j] = 0.f;
+    }
+    for (int s = 0; s < k; ++s) {
+      const int p = dst_pos[t * k + s];
+      if (p >= 0) {
+        float f[V];
+        unpack16<T>(dx_p[(long)p * row_vecs + c], f);
+#pragma unroll
+        for (int j = 0; j < V; ++j) acc[j] += f[j];
+      }
+    }
+    dx[t * row_vecs + c] = pack16<T>(acc);
+  }
+}
+
+static inline int n_chunks_of(const dynmo_desc* d) { return (int)(((int64_t)d->T * d->k + kChunk - 1) / kChunk); }
+
+}  // namespace dynmo
+
+using namespace dynmo;
+
+extern "C" size_t dynmo_permute_workspace_bytes(const dynmo_desc* d) {
+  if (check_desc(d)) return 0;
+  return align_up((size_t)(n_chunks_of(d) > 0 ? n_chunks_of(d) : 1) * d->E * sizeof(int32_t), 256);
+}
+
+extern "C" int32_t dynmo_permute(const dynmo_desc* d, const void* x, const int32_t* expert_idx, void* x_p,
+                                 int32_t* seg_offsets, int32_t* src_slot, int32_t* dst_pos, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  int32_t rc = check_desc(d);
+  if (rc) return rc;
+  if (!x || !expert_idx || !x_p || !seg_offsets || !src_slot || !dst_pos || !workspace) return DYNMO_EINVAL;
+  if (workspace_bytes < dynmo_permute_workspace_bytes(d)) return DYNMO_EWORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  const int n_slots = d->T * d->k;
+  const int nc = n_chunks_of(d);
+  int32_t* chunk_counts = (int32_t*)workspace;
+  if (nc > 0) {
+    permute_count_kernel<<<dim3(nc), dim3(kChunkThreads), 0, st>>>(expert_idx, n_slots, d->E, chunk_counts);
+    DYNMO_LAUNCH_CHECK();
+  }
+  permute_scan_kernel<<<dim3(1), dim3(2 * kMaxExperts), 0, st>>>(chunk_counts, nc, d->E, seg_offsets);
+  DYNMO_LAUNCH_CHECK();
+  if (nc > 0) {
+    permute_scatter_kernel<<<dim3(nc), dim3(kChunkThreads), 0, st>>>(expert_idx, n_slots, d->E, chunk_counts, src_slot,
+                                                                     dst_pos);
+    DYNMO_LAUNCH_CHECK();
+    const int row_vecs = (int)((size_t)d->H * elem_bytes(d->dtype) / 16);
+    const unsigned blocks = (unsigned)(((int64_t)d->T * 64 + 255) / 256);
+    if (d->k <= 2)
+      permute_rows_kernel<2><<<dim3(blocks), dim3(256), 0, st>>>((const u32x4*)x, dst_pos, (u32x4*)x_p, d->T, d->k, row_vecs);
+    else if (d->k <= 8)
+      permute_rows_kernel<8><<<dim3(blocks), dim3(256), 0, st>>>((const u32x4*)x, dst_pos, (u32x4*)x_p, d->T, d->k, row_vecs);
+    else
+      permute_rows_kernel<kMaxExperts><<<dim3(blocks), dim3(256), 0, st>>>((const u32x4*)x, dst_pos, (u32x4*)x_p, d->T, d->k,
+                                                                          row_vecs);
+    DYNMO_LAUNCH_CHECK();
+  }
+  return DYNMO_OK;
+}
+
+extern "C" int32_t dynmo_permute_bwd(const dynmo_desc* d, const void* dx_p, const int32_t* dst_pos, const void* dbase,
+                                     void* dx, void* stream) {
+  int32_t rc = check_desc(d);
+  if (rc) return rc;
+  if (!dx_p || !dst_pos || !dx) return DYNMO_EINVAL;
+  if (d->T == 0) return DYNMO_OK;
+  hipStream_t st = (hipStream_t)stream;
+  const int row_vecs = (int)((size_t)d->H * elem_bytes(d->dtype) / 16);
+  const unsigned blocks = (unsigned)(((int64_t)d->T * 64 + 255) / 256);
+  if (d->dtype == DYNMO_BF16)
+    permute_bwd_kernel<bf16_t><<<dim3(blocks), dim3(256), 0, st>>>((const u32x4*)dx_p, dst_pos, (const u32x4*)dbase,
+                                                                   (u32x4*)dx, d->T, d->k, row_vecs);
+  else
+    permute_bwd_kernel<float><<<dim3(blocks), dim3(256), 0, st>>>((const u32x4*)dx_p, dst_pos, (const u32x4*)dbase,
+                                                                  (u32x4*)dx, d->T, d->k, row_vecs);
+  DYNMO_LAUNCH_CHECK();
+  return DYNMO_OK;
+}

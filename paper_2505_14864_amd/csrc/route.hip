@@ -1,0 +1,283 @@
+// Routing kernels: token-choice top-k (MoE), per-sequence capacity top-k
+// (Mixture-of-Depths), early-exit activity, and the gate backward passes.
+#include "common.h"
+
+namespace dynmo {
+
+// ---------------------------------------------------------------------------
+// Top-k over E <= 64 logits.  A token owns LPT = pow2ceil(E) adjacent lanes of a
+// wavefront, one logit per lane, so a 64-lane wavefront routes 64/LPT tokens and
+// the logit loads are contiguous across the wavefront.  Each of the k rounds is
+// a butterfly arg-max over the token's lanes with the order
+// (value descending, expert index ascending); the winner is then retired.
+// ---------------------------------------------------------------------------
+struct Cand {
+  float v;
+  int idx;  // INT_MAX when the lane holds no live candidate
+};
+
+__device__ __forceinline__ bool better(const Cand& a, const Cand& b) {
+  const bool av = a.idx != 0x7fffffff, bv = b.idx != 0x7fffffff;
+  if (av != bv) return av;
+  if (!av) return false;
+  return a.v > b.v || (a.v == b.v && a.idx < b.idx);
+}
+
+template <int LPT>
+__global__ __launch_bounds__(256) void route_topk_kernel(const float* __restrict__ logits, int32_t* __restrict__ expert_idx,
+                                                         float* __restrict__ gate_w, int T, int E, int k) {
+  constexpr int TOK_PER_WAVE = 64 / LPT;
+  const int lane = threadIdx.x & 63;
+  const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int j = lane % LPT;
+  const long t = (long)wave * TOK_PER_WAVE + lane / LPT;
+  const bool live = t < T && j < E;
+  Cand mine;
+  mine.v = live ? logits[t * E + j] : 0.f;
+  mine.idx = live ? j : 0x7fffffff;
+  float my_val = 0.f, top = 0.f, denom = 0.f;
+  int my_idx = 0;
+  for (int s = 0; s < k; ++s) {
+    Cand best = mine;
+#pragma unroll
+    for (int m = 1; m < LPT; m <<= 1) {
+      Cand o;
+      o.v = __shfl_xor(best.v, m, 64);
+      o.idx = __shfl_xor(best.idx, m, 64);
+      if (better(o, best)) best = o;
+    }
+    if (s == 0) top = best.v;
+    denom += __expf(best.v - top);
+    if (j == s) {
+      my_val = best.v;
+      my_idx = best.idx;
+    }
+    if (mine.idx == best.idx) mine.idx = 0x7fffffff;  // retire the winner
+  }
+  if (t < T && j < k) {
+    expert_idx[t * k + j] = my_idx;
+    gate_w[t * k + j] = __expf(my_val - top) / denom;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Capacity top-k: one workgroup per sequence.  A 4-pass, 8-bit-per-pass radix
+// select on order-preserving integer keys finds the cap-th largest score; ties
+// at that value are resolved by ascending position with an ordered block scan.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t score_key(float f) {
+  uint32_t u = __float_as_uint(f);
+  if (u == 0x80000000u) u = 0;  // -0.0 equals +0.0
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+constexpr int kCapThreads = 1024;
+
+__global__ __launch_bounds__(kCapThreads) void route_capacity_kernel(const float* __restrict__ scores,
+                                                                     int32_t* __restrict__ expert_idx,
+                                                                     float* __restrict__ gate_w, int S, int cap) {
+  __shared__ int hist[256];
+  __shared__ uint32_t sh_prefix;
+  __shared__ int sh_remaining;
+  __shared__ int wave_cnt[kCapThreads / 64];
+  __shared__ int sh_running;
+  const float* sc = scores + (long)blockIdx.x * S;
+  int32_t* ei = expert_idx + (long)blockIdx.x * S;
+  float* gw = gate_w + (long)blockIdx.x * S;
+  const int tid = threadIdx.x;
+
+  if (cap <= 0 || cap >= S) {
+    const bool all = cap >= S;
+    for (int i = tid; i < S; i += kCapThreads) {
+      ei[i] = all ? 0 : -1;
+      gw[i] = all ? sigmoidf_(sc[i]) : 0.f;
+    }
+    return;
+  }
+
+  // radix select: after the passes, sh_prefix is the key of the cap-th largest
+  // score and sh_remaining how many keys equal to it are still to be taken.
+  if (tid == 0) {
+    sh_prefix = 0;
+    sh_remaining = cap;
+  }
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    const uint32_t prefix = sh_prefix;
+    const uint32_t himask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
+    for (int i = tid; i < S; i += kCapThreads) {
+      const uint32_t key = score_key(sc[i]);
+      if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 0xff], 1);
+    }
+    __syncthreads();
+    if (tid == 0) {
+      int remaining = sh_remaining;
+      int b = 255;
+      for (; b > 0; --b) {
+        if (hist[b] >= remaining) break;
+        remaining -= hist[b];
+      }
+      sh_prefix = prefix | ((uint32_t)b << shift);
+      sh_remaining = remaining;
+    }
+    __syncthreads();
+  }
+  const uint32_t thr = sh_prefix;
+  const int need_equal = sh_remaining;
+  if (tid == 0) sh_running = 0;
+  __syncthreads();
+
+  const int lane = tid & 63, wv = tid >> 6;
+  for (int base = 0; base < S; base += kCapThreads) {
+    const int i = base + tid;
+    float s = 0.f;
+    uint32_t key = 0;
+    if (i < S) {
+      s = sc[i];
+      key = score_key(s);
+    }
+    const bool eq = i < S && key == thr;
+    const unsigned long long m = __ballot(eq);
+    if (lane == 0) wave_cnt[wv] = __popcll(m);
+    __syncthreads();
+    int before = sh_running + __popcll(m & ((1ull << lane) - 1ull));
+    int total = 0;
+    for (int w = 0; w < kCapThreads / 64; ++w) {
+      const int c = wave_cnt[w];
+      if (w < wv) before += c;
+      total += c;
+    }
+    if (i < S) {
+      const bool sel = key > thr || (eq && before < need_equal);
+      ei[i] = sel ? 0 : -1;
+      gw[i] = sel ? sigmoidf_(s) : 0.f;
+    }
+    __syncthreads();
+    if (tid == 0) sh_running += total;
+    __syncthreads();
+  }
+}
+
+__global__ void route_active_kernel(const int32_t* __restrict__ exit_layer, int layer, int32_t* __restrict__ expert_idx,
+                                    float* __restrict__ gate_w, int T) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < T) {
+    const bool act = exit_layer[t] >= layer;
+    expert_idx[t] = act ? 0 : -1;
+    gate_w[t] = act ? 1.f : 0.f;
+  }
+}
+
+__global__ void route_topk_bwd_kernel(const float* __restrict__ dgate, const float* __restrict__ gate_w,
+                                      const int32_t* __restrict__ expert_idx, float* __restrict__ dlogits, int T, int E,
+                                      int k) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= T) return;
+  float inner = 0.f;
+  for (int s = 0; s < k; ++s) inner += gate_w[(long)t * k + s] * dgate[(long)t * k + s];
+  for (int e = 0; e < E; ++e) dlogits[(long)t * E + e] = 0.f;
+  for (int s = 0; s < k; ++s) {
+    const int e = expert_idx[(long)t * k + s];
+    if (e >= 0 && e < E) dlogits[(long)t * E + e] = gate_w[(long)t * k + s] * (dgate[(long)t * k + s] - inner);
+  }
+}
+
+__global__ void route_capacity_bwd_kernel(const float* __restrict__ dgate, const float* __restrict__ scores,
+                                          const int32_t* __restrict__ expert_idx, float* __restrict__ dscores, int T) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= T) return;
+  float r = 0.f;
+  if (expert_idx[t] >= 0) {
+    const float s = sigmoidf_(scores[t]);
+    r = s * (1.f - s) * dgate[t];
+  }
+  dscores[t] = r;
+}
+
+template <int LPT>
+static int32_t launch_topk(const dynmo_desc* d, const float* logits, int32_t* ei, float* gw, hipStream_t st) {
+  const long tok_per_block = (256 / 64) * (64 / LPT);
+  const long blocks = (d->T + tok_per_block - 1) / tok_per_block;
+  if (blocks > 0) {
+    route_topk_kernel<LPT><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(logits, ei, gw, d->T, d->E, d->k);
+    DYNMO_LAUNCH_CHECK();
+  }
+  return DYNMO_OK;
+}
+
+}  // namespace dynmo
+
+using namespace dynmo;
+
+extern "C" int32_t dynmo_route_topk(const dynmo_desc* d, const float* logits, int32_t* expert_idx, float* gate_w,
+                                    void* stream) {
+  int32_t rc = check_desc(d);
+  if (rc) return rc;
+  if (!logits || !expert_idx || !gate_w) return DYNMO_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  const int E = d->E;
+  if (E <= 1) return launch_topk<1>(d, logits, expert_idx, gate_w, st);
+  if (E <= 2) return launch_topk<2>(d, logits, expert_idx, gate_w, st);
+  if (E <= 4) return launch_topk<4>(d, logits, expert_idx, gate_w, st);
+  if (E <= 8) return launch_topk<8>(d, logits, expert_idx, gate_w, st);
+  if (E <= 16) return launch_topk<16>(d, logits, expert_idx, gate_w, st);
+  if (E <= 32) return launch_topk<32>(d, logits, expert_idx, gate_w, st);
+  return launch_topk<64>(d, logits, expert_idx, gate_w, st);
+}
+
+extern "C" int32_t dynmo_route_capacity(const dynmo_desc* d, const float* scores, int32_t B, int32_t S, int32_t cap,
+                                        int32_t* expert_idx, float* gate_w, void* stream) {
+  int32_t rc = check_desc(d);
+  if (rc) return rc;
+  if (!scores || !expert_idx || !gate_w) return DYNMO_EINVAL;
+  if (d->E != 1 || d->k != 1 || B < 0 || S <= 0 || (int64_t)B * S != d->T || cap < 0 || cap > S) return DYNMO_EINVAL;
+  if (B > 0) {
+    route_capacity_kernel<<<dim3((unsigned)B), dim3(kCapThreads), 0, (hipStream_t)stream>>>(scores, expert_idx, gate_w, S,
+                                                                                            cap);
+    DYNMO_LAUNCH_CHECK();
+  }
+  return DYNMO_OK;
+}
+
+extern "C" int32_t dynmo_route_active(const dynmo_desc* d, const int32_t* exit_layer, int32_t layer,
+                                      int32_t* expert_idx, float* gate_w, void* stream) {
+  int32_t rc = check_desc(d);
+  if (rc) return rc;
+  if (!exit_layer || !expert_idx || !gate_w) return DYNMO_EINVAL;
+  if (d->E != 1 || d->k != 1) return DYNMO_EINVAL;
+  if (d->T > 0) {
+    route_active_kernel<<<dim3((d->T + 255) / 256), dim3(256), 0, (hipStream_t)stream>>>(exit_layer, layer, expert_idx,
+                                                                                         gate_w, d->T);
+    DYNMO_LAUNCH_CHECK();
+  }
+  return DYNMO_OK;
+}
+
+extern "C" int32_t dynmo_route_topk_bwd(const dynmo_desc* d, const float* dgate, const float* gate_w,
+                                        const int32_t* expert_idx, float* dlogits, void* stream) {
+  int32_t rc = check_desc(d);
+  if (rc) return rc;
+  if (!dgate || !gate_w || !expert_idx || !dlogits) return DYNMO_EINVAL;
+  if (d->T > 0) {
+    route_topk_bwd_kernel<<<dim3((d->T + 255) / 256), dim3(256), 0, (hipStream_t)stream>>>(dgate, gate_w, expert_idx,
+                                                                                           dlogits, d->T, d->E, d->k);
+    DYNMO_LAUNCH_CHECK();
+  }
+  return DYNMO_OK;
+}
+
+extern "C" int32_t dynmo_route_capacity_bwd(const dynmo_desc* d, const float* dgate, const float* scores,
+                                            const int32_t* expert_idx, float* dscores, void* stream) {
+  int32_t rc = check_desc(d);
+  if (rc) return rc;
+  if (!dgate || !scores || !expert_idx || !dscores) return DYNMO_EINVAL;
+  if (d->E != 1 || d->k != 1) return DYNMO_EINVAL;
+  if (d->T > 0) {
+    route_capacity_bwd_kernel<<<dim3((d->T + 255) / 256), dim3(256), 0, (hipStream_t)stream>>>(dgate, scores, expert_idx,
+                                                                                               dscores, d->T);
+    DYNMO_LAUNCH_CHECK();
+  }
+  return DYNMO_OK;
+}
