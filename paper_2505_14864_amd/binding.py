@@ -52,7 +52,7 @@ SIGNATURES = {
     "dynmo_grouped_ffn_fwd_workspace_bytes": (C.c_size_t, [_D]),
     "dynmo_grouped_ffn_fwd": (_I, [_D, _P, _P, _P, _P, _P, _P, _P, _P, _P, C.c_size_t, _P]),
     "dynmo_grouped_ffn_bwd_workspace_bytes": (C.c_size_t, [_D]),
-    "dynmo_grouped_ffn_bwd": (_I, [_D] + [_P] * 14 + [C.c_size_t, _P]),
+    "dynmo_grouped_ffn_bwd": (_I, [_D] + [_P] * 13 + [C.c_size_t, _P]),
     "dynmo_combine": (_I, [_D, _P, _P, _P, _P, _P, _P]),
     "dynmo_combine_bwd": (_I, [_D, _P, _P, _P, _P, _P, _P, _P]),
     "dynmo_layer_load": (_I, [_D, _P, C.c_double, C.POINTER(C.c_int32), C.POINTER(C.c_double), _P]),

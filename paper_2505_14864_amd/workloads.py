@@ -85,18 +85,31 @@ def widen_bf16(bits: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
-def _normal(seed, tag, shape, sigma, dtype, part=0):
-    a = _rng(seed, tag, part).standard_normal(shape, dtype=np.float32)
-    if sigma != 1.0:
-        a *= np.float32(sigma)
-    return a if dtype == "f32" else round_to_bf16_bits(a)
+_CHUNK = 1 << 20  # elements drawn and converted at a time (keeps temporaries in cache)
+
+
+def _normal(seed, tag, shape, sigma, dtype, part=0, out=None):
+    """sigma * N(0,1) draws from the tensor's own sub-stream, in C order."""
+    rng = _rng(seed, tag, part)
+    n = int(np.prod(shape))
+    if out is None:
+        out = np.empty(shape, dtype=np.float32 if dtype == "f32" else np.uint16)
+    flat = out.reshape(-1)
+    sig = np.float32(sigma)
+    for lo in range(0, n, _CHUNK):
+        hi = min(n, lo + _CHUNK)
+        a = rng.standard_normal(hi - lo, dtype=np.float32)
+        if sigma != 1.0:
+            a *= sig
+        flat[lo:hi] = a if dtype == "f32" else round_to_bf16_bits(a)
+    return out
 
 
 def _per_part(seed, tag, parts, shape, sigma, dtype, threads):
     out = np.empty((parts,) + tuple(shape), dtype=np.float32 if dtype == "f32" else np.uint16)
 
     def job(p):
-        out[p] = _normal(seed, tag, shape, sigma, dtype, part=p)
+        _normal(seed, tag, shape, sigma, dtype, part=p, out=out[p])
 
     if threads > 1 and parts > 1:
         with ThreadPoolExecutor(max_workers=threads) as ex:

@@ -18,6 +18,22 @@ def declared_symbols():
     return sorted(set(re.findall(r"\b(dynmo_[a-z0-9_]+)\s*\(", text)))
 
 
+def declared_arity():
+    text = open(os.path.join(ROOT, "include", "dynmo.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    out = {}
+    for name, args in re.findall(r"\b(dynmo_[a-z0-9_]+)\s*\(([^)]*)\)\s*;", text):
+        args = args.strip()
+        out[name] = 0 if args in ("", "void") else len(args.split(","))
+    return out
+
+
+def test_binding_arity_matches_header():
+    arity = declared_arity()
+    for name, (_, argtypes) in B.SIGNATURES.items():
+        assert arity[name] == len(argtypes), name
+
+
 def test_library_exports_every_declared_symbol():
     names = declared_symbols()
     assert len(names) >= 20
