@@ -24,7 +24,7 @@
  *     Logits, scores, gate weights and their gradients are always float.
  *   - weights: Wg, Wu are [E, F, H]; Wd is [E, H, F].
  *   - limits: 1 <= k <= E <= 64 (k <= 8 for the combine calls); for DYNMO_BF16
- *     H and F must be multiples of 8.  Violations return DYNMO_EINVAL /
+ *     H and F must be multiples of 8, for DYNMO_F32 H a multiple of 4.  Violations return DYNMO_EINVAL /
  *     DYNMO_EUNSUPPORTED before anything is launched.
  *   - NaN in logits or scores is undefined input.
  */
@@ -181,6 +181,21 @@ int32_t dynmo_stage_loads(const double* loads_host, int32_t L, const int32_t* bo
 
 /* Imbalance (L_max - L_min) / mean(L) of Sec. 2, Eq. 1-2. */
 int32_t dynmo_imbalance(const double* stage_loads_host, int32_t S, double* imbalance_host);
+
+/* ---- profiling step ------------------------------------------------------ */
+
+/* The paper's profiling step (Sec. 3.1, Sec. 4: the iteration after a change is
+ * timed per layer and the times feed the "by Time" balancers).  While enabled,
+ * every kernel the library launches is bracketed by a hipEvent pair on its
+ * stream; totals are kept per kernel role (dynmo_profile_kernel_name) and are
+ * process-wide.  dynmo_profile_read waits for the recorded launches of that role
+ * to finish, then returns their summed duration in milliseconds and their count
+ * (HOST pointers).  dynmo_profile_reset waits likewise and zeroes all totals. */
+int32_t dynmo_profile_enable(int32_t on);
+int32_t dynmo_profile_reset(void);
+int32_t dynmo_profile_kernel_count(void);
+const char* dynmo_profile_kernel_name(int32_t id);
+int32_t dynmo_profile_read(int32_t id, double* total_ms_host, int64_t* launches_host);
 
 #ifdef __cplusplus
 }

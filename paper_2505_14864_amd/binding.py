@@ -60,6 +60,11 @@ SIGNATURES = {
     "dynmo_uniform_bounds": (_I, [_I, _I, C.POINTER(C.c_int32)]),
     "dynmo_stage_loads": (_I, [C.POINTER(C.c_double), _I, C.POINTER(C.c_int32), _I, C.POINTER(C.c_double)]),
     "dynmo_imbalance": (_I, [C.POINTER(C.c_double), _I, C.POINTER(C.c_double)]),
+    "dynmo_profile_enable": (_I, [_I]),
+    "dynmo_profile_reset": (_I, []),
+    "dynmo_profile_kernel_count": (_I, []),
+    "dynmo_profile_kernel_name": (C.c_char_p, [_I]),
+    "dynmo_profile_read": (_I, [_I, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
 }
 
 _lib = None
@@ -222,3 +227,29 @@ def dynmo_imbalance(stage_loads):
     r = C.c_double()
     _check("dynmo_imbalance", lib().dynmo_imbalance(_darr(stage_loads), len(stage_loads), C.byref(r)))
     return r.value
+
+
+# ---- profiling step ---------------------------------------------------------
+
+def dynmo_profile_enable(on):
+    _check("dynmo_profile_enable", lib().dynmo_profile_enable(1 if on else 0))
+
+
+def dynmo_profile_reset():
+    _check("dynmo_profile_reset", lib().dynmo_profile_reset())
+
+
+def dynmo_profile_kernel_count():
+    return lib().dynmo_profile_kernel_count()
+
+
+def dynmo_profile_kernel_name(i):
+    return lib().dynmo_profile_kernel_name(i).decode()
+
+
+def dynmo_profile_read(i):
+    """Returns (total_ms, launches) of kernel role i; waits for those launches."""
+    ms = C.c_double()
+    n = C.c_int64()
+    _check("dynmo_profile_read", lib().dynmo_profile_read(i, C.byref(ms), C.byref(n)))
+    return ms.value, n.value

@@ -2,6 +2,7 @@
 // backward.  Both are HBM-bound row kernels: one wavefront per token, 16-byte
 // accesses, fp32 arithmetic, slots summed in ascending order.
 #include "common.h"
+#include "profile.h"
 
 namespace dynmo {
 
@@ -115,6 +116,30 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const u32x4* __restric
   }
 }
 
+template <typename T>
+static int32_t launch_combine(const dynmo_desc* d, const void* y_p, const int32_t* dst_pos, const float* gate_w,
+                              const void* base, void* out, hipStream_t st) {
+  const int row_vecs = (int)((size_t)d->H * sizeof(T) / 16);
+  const unsigned blocks = (unsigned)(((int64_t)d->T * 64 + 255) / 256);
+  DYNMO_TIMED_LAUNCH(K_COMBINE, st,
+                     combine_kernel<T><<<dim3(blocks), dim3(256), 0, st>>>((const u32x4*)y_p, dst_pos, gate_w,
+                                                                           (const u32x4*)base, (u32x4*)out, d->T, d->k,
+                                                                           row_vecs));
+  return DYNMO_OK;
+}
+
+template <typename T>
+static int32_t launch_combine_bwd(const dynmo_desc* d, const void* dout, const void* y_p, const int32_t* dst_pos,
+                                  const float* gate_w, void* dy_p, float* dgate, hipStream_t st) {
+  const int row_vecs = (int)((size_t)d->H * sizeof(T) / 16);
+  const unsigned blocks = (unsigned)(((int64_t)d->T * 64 + 255) / 256);
+  DYNMO_TIMED_LAUNCH(K_COMBINE_BWD, st,
+                     combine_bwd_kernel<T><<<dim3(blocks), dim3(256), 0, st>>>((const u32x4*)dout, (const u32x4*)y_p,
+                                                                               dst_pos, gate_w, (u32x4*)dy_p, dgate, d->T,
+                                                                               d->k, row_vecs));
+  return DYNMO_OK;
+}
+
 }  // namespace dynmo
 
 using namespace dynmo;
@@ -128,16 +153,8 @@ extern "C" int32_t dynmo_combine(const dynmo_desc* d, const void* y_p, const int
   if (d->k > kMaxCombineSlots) return DYNMO_EUNSUPPORTED;
   if (d->T == 0) return DYNMO_OK;
   hipStream_t st = (hipStream_t)stream;
-  const int row_vecs = (int)((size_t)d->H * elem_bytes(d->dtype) / 16);
-  const unsigned blocks = (unsigned)(((int64_t)d->T * 64 + 255) / 256);
-  if (d->dtype == DYNMO_BF16)
-    combine_kernel<bf16_t><<<dim3(blocks), dim3(256), 0, st>>>((const u32x4*)y_p, dst_pos, gate_w, (const u32x4*)base,
-                                                               (u32x4*)out, d->T, d->k, row_vecs);
-  else
-    combine_kernel<float><<<dim3(blocks), dim3(256), 0, st>>>((const u32x4*)y_p, dst_pos, gate_w, (const u32x4*)base,
-                                                              (u32x4*)out, d->T, d->k, row_vecs);
-  DYNMO_LAUNCH_CHECK();
-  return DYNMO_OK;
+  return d->dtype == DYNMO_BF16 ? launch_combine<bf16_t>(d, y_p, dst_pos, gate_w, base, out, st)
+                                : launch_combine<float>(d, y_p, dst_pos, gate_w, base, out, st);
 }
 
 extern "C" int32_t dynmo_combine_bwd(const dynmo_desc* d, const void* dout, const void* y_p, const int32_t* dst_pos,
@@ -148,14 +165,6 @@ extern "C" int32_t dynmo_combine_bwd(const dynmo_desc* d, const void* dout, cons
   if (d->k > kMaxCombineSlots) return DYNMO_EUNSUPPORTED;
   if (d->T == 0) return DYNMO_OK;
   hipStream_t st = (hipStream_t)stream;
-  const int row_vecs = (int)((size_t)d->H * elem_bytes(d->dtype) / 16);
-  const unsigned blocks = (unsigned)(((int64_t)d->T * 64 + 255) / 256);
-  if (d->dtype == DYNMO_BF16)
-    combine_bwd_kernel<bf16_t><<<dim3(blocks), dim3(256), 0, st>>>((const u32x4*)dout, (const u32x4*)y_p, dst_pos, gate_w,
-                                                                   (u32x4*)dy_p, dgate, d->T, d->k, row_vecs);
-  else
-    combine_bwd_kernel<float><<<dim3(blocks), dim3(256), 0, st>>>((const u32x4*)dout, (const u32x4*)y_p, dst_pos, gate_w,
-                                                                  (u32x4*)dy_p, dgate, d->T, d->k, row_vecs);
-  DYNMO_LAUNCH_CHECK();
-  return DYNMO_OK;
+  return d->dtype == DYNMO_BF16 ? launch_combine_bwd<bf16_t>(d, dout, y_p, dst_pos, gate_w, dy_p, dgate, st)
+                                : launch_combine_bwd<float>(d, dout, y_p, dst_pos, gate_w, dy_p, dgate, st);
 }

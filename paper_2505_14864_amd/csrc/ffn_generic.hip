@@ -5,6 +5,7 @@
 // loop serves X W^T, dY W, and the token-contracted dY^T A products.
 #include "common.h"
 #include "ffn.h"
+#include "profile.h"
 
 namespace dynmo {
 
@@ -167,14 +168,12 @@ static int32_t fwd_generic_t(const dynmo_desc* d, const void* x_p, const int32_t
   const int m_tiles = max_m_tiles(d, GT);
   if (m_tiles == 0) return DYNMO_OK;
   const long FH = (long)d->F * d->H;
-  gateup_generic_kernel<T><<<dim3((d->F + GT - 1) / GT, m_tiles), dim3(256), 0, st>>>(
-      (const T*)x_p, seg, (const T*)Wg, (const T*)Wu, (T*)G, (T*)U, (T*)A, d->E, d->H, d->F);
-  DYNMO_LAUNCH_CHECK();
+  DYNMO_TIMED_LAUNCH(K_FFN_GATEUP, st, gateup_generic_kernel<T><<<dim3((d->F + GT - 1) / GT, m_tiles), dim3(256), 0, st>>>(
+      (const T*)x_p, seg, (const T*)Wg, (const T*)Wu, (T*)G, (T*)U, (T*)A, d->E, d->H, d->F));
   // Y = A Wd^T : B(n=h, k=f) = Wd[e][h*F + f]
-  seg_gemm_generic_kernel<T, EPI_STORE><<<dim3((d->H + GT - 1) / GT, m_tiles), dim3(256), 0, st>>>(
+  DYNMO_TIMED_LAUNCH(K_FFN_DOWN, st, seg_gemm_generic_kernel<T, EPI_STORE><<<dim3((d->H + GT - 1) / GT, m_tiles), dim3(256), 0, st>>>(
       seg, d->E, d->H, d->F, (const T*)A, (const T*)Wd, nullptr, nullptr, d->F, FH, d->F, 1, (T*)y_p, nullptr, nullptr,
-      nullptr, nullptr, nullptr);
-  DYNMO_LAUNCH_CHECK();
+      nullptr, nullptr, nullptr));
   return DYNMO_OK;
 }
 
@@ -187,23 +186,18 @@ static int32_t bwd_generic_t(const dynmo_desc* d, const void* dy_p, const void* 
   const unsigned tf = (d->F + GT - 1) / GT, th = (d->H + GT - 1) / GT;
   if (m_tiles > 0) {
     // dA = dY Wd : B(n=f, k=h) = Wd[e][h*F + f]; epilogue gives A, dG, dU
-    seg_gemm_generic_kernel<T, EPI_SWIGLU_BWD><<<dim3(tf, m_tiles), dim3(256), 0, st>>>(
+    DYNMO_TIMED_LAUNCH(K_FFN_DA, st, seg_gemm_generic_kernel<T, EPI_SWIGLU_BWD><<<dim3(tf, m_tiles), dim3(256), 0, st>>>(
         seg, d->E, d->F, d->H, (const T*)dy_p, (const T*)Wd, nullptr, nullptr, d->H, FH, 1, d->F, nullptr, (const T*)G,
-        (const T*)U, (T*)dG, (T*)dU, (T*)A);
-    DYNMO_LAUNCH_CHECK();
+        (const T*)U, (T*)dG, (T*)dU, (T*)A));
     // dX = dG Wg + dU Wu : B(n=h, k=f) = W[e][f*H + h]
-    seg_gemm_generic_kernel<T, EPI_STORE><<<dim3(th, m_tiles), dim3(256), 0, st>>>(
+    DYNMO_TIMED_LAUNCH(K_FFN_DX, st, seg_gemm_generic_kernel<T, EPI_STORE><<<dim3(th, m_tiles), dim3(256), 0, st>>>(
         seg, d->E, d->H, d->F, (const T*)dG, (const T*)Wg, (const T*)dU, (const T*)Wu, d->F, FH, 1, d->H, (T*)dx_p, nullptr,
-        nullptr, nullptr, nullptr, nullptr);
-    DYNMO_LAUNCH_CHECK();
+        nullptr, nullptr, nullptr, nullptr));
   }
   // The weight gradients are written for every expert, rows or not.
-  dw_generic_kernel<T><<<dim3(tf, th, d->E), dim3(256), 0, st>>>(seg, d->H, d->F, (const T*)dy_p, (const T*)A, (T*)dWd);
-  DYNMO_LAUNCH_CHECK();
-  dw_generic_kernel<T><<<dim3(th, tf, d->E), dim3(256), 0, st>>>(seg, d->F, d->H, (const T*)dG, (const T*)x_p, (T*)dWg);
-  DYNMO_LAUNCH_CHECK();
-  dw_generic_kernel<T><<<dim3(th, tf, d->E), dim3(256), 0, st>>>(seg, d->F, d->H, (const T*)dU, (const T*)x_p, (T*)dWu);
-  DYNMO_LAUNCH_CHECK();
+  DYNMO_TIMED_LAUNCH(K_FFN_DWD, st, dw_generic_kernel<T><<<dim3(tf, th, d->E), dim3(256), 0, st>>>(seg, d->H, d->F, (const T*)dy_p, (const T*)A, (T*)dWd));
+  DYNMO_TIMED_LAUNCH(K_FFN_DWG, st, dw_generic_kernel<T><<<dim3(th, tf, d->E), dim3(256), 0, st>>>(seg, d->F, d->H, (const T*)dG, (const T*)x_p, (T*)dWg));
+  DYNMO_TIMED_LAUNCH(K_FFN_DWU, st, dw_generic_kernel<T><<<dim3(th, tf, d->E), dim3(256), 0, st>>>(seg, d->F, d->H, (const T*)dU, (const T*)x_p, (T*)dWu));
   return DYNMO_OK;
 }
 

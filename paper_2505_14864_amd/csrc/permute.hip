@@ -5,6 +5,7 @@
 // row is read once and written to its (up to k) destinations with 16-byte
 // accesses.
 #include "common.h"
+#include "profile.h"
 
 namespace dynmo {
 
@@ -180,6 +181,28 @@ __global__ __launch_bounds__(256) void permute_bwd_kernel(const u32x4* __restric
 
 static inline int n_chunks_of(const dynmo_desc* d) { return (int)(((int64_t)d->T * d->k + kChunk - 1) / kChunk); }
 
+template <int MAXK>
+static int32_t launch_rows(const dynmo_desc* d, const void* x, const int32_t* dst_pos, void* x_p, hipStream_t st) {
+  const int row_vecs = (int)((size_t)d->H * elem_bytes(d->dtype) / 16);
+  const unsigned blocks = (unsigned)(((int64_t)d->T * 64 + 255) / 256);
+  DYNMO_TIMED_LAUNCH(K_PERMUTE_ROWS, st,
+                     permute_rows_kernel<MAXK><<<dim3(blocks), dim3(256), 0, st>>>((const u32x4*)x, dst_pos, (u32x4*)x_p,
+                                                                                   d->T, d->k, row_vecs));
+  return DYNMO_OK;
+}
+
+template <typename T>
+static int32_t launch_permute_bwd(const dynmo_desc* d, const void* dx_p, const int32_t* dst_pos, const void* dbase,
+                                  void* dx, hipStream_t st) {
+  const int row_vecs = (int)((size_t)d->H * sizeof(T) / 16);
+  const unsigned blocks = (unsigned)(((int64_t)d->T * 64 + 255) / 256);
+  DYNMO_TIMED_LAUNCH(K_PERMUTE_BWD, st,
+                     permute_bwd_kernel<T><<<dim3(blocks), dim3(256), 0, st>>>((const u32x4*)dx_p, dst_pos,
+                                                                               (const u32x4*)dbase, (u32x4*)dx, d->T, d->k,
+                                                                               row_vecs));
+  return DYNMO_OK;
+}
+
 }  // namespace dynmo
 
 using namespace dynmo;
@@ -201,27 +224,19 @@ extern "C" int32_t dynmo_permute(const dynmo_desc* d, const void* x, const int32
   const int nc = n_chunks_of(d);
   int32_t* chunk_counts = (int32_t*)workspace;
   if (nc > 0) {
-    permute_count_kernel<<<dim3(nc), dim3(kChunkThreads), 0, st>>>(expert_idx, n_slots, d->E, chunk_counts);
-    DYNMO_LAUNCH_CHECK();
+    DYNMO_TIMED_LAUNCH(K_PERMUTE_COUNT, st,
+                       permute_count_kernel<<<dim3(nc), dim3(kChunkThreads), 0, st>>>(expert_idx, n_slots, d->E,
+                                                                                      chunk_counts));
   }
-  permute_scan_kernel<<<dim3(1), dim3(2 * kMaxExperts), 0, st>>>(chunk_counts, nc, d->E, seg_offsets);
-  DYNMO_LAUNCH_CHECK();
-  if (nc > 0) {
-    permute_scatter_kernel<<<dim3(nc), dim3(kChunkThreads), 0, st>>>(expert_idx, n_slots, d->E, chunk_counts, src_slot,
-                                                                     dst_pos);
-    DYNMO_LAUNCH_CHECK();
-    const int row_vecs = (int)((size_t)d->H * elem_bytes(d->dtype) / 16);
-    const unsigned blocks = (unsigned)(((int64_t)d->T * 64 + 255) / 256);
-    if (d->k <= 2)
-      permute_rows_kernel<2><<<dim3(blocks), dim3(256), 0, st>>>((const u32x4*)x, dst_pos, (u32x4*)x_p, d->T, d->k, row_vecs);
-    else if (d->k <= 8)
-      permute_rows_kernel<8><<<dim3(blocks), dim3(256), 0, st>>>((const u32x4*)x, dst_pos, (u32x4*)x_p, d->T, d->k, row_vecs);
-    else
-      permute_rows_kernel<kMaxExperts><<<dim3(blocks), dim3(256), 0, st>>>((const u32x4*)x, dst_pos, (u32x4*)x_p, d->T, d->k,
-                                                                          row_vecs);
-    DYNMO_LAUNCH_CHECK();
-  }
-  return DYNMO_OK;
+  DYNMO_TIMED_LAUNCH(K_PERMUTE_SCAN, st,
+                     permute_scan_kernel<<<dim3(1), dim3(2 * kMaxExperts), 0, st>>>(chunk_counts, nc, d->E, seg_offsets));
+  if (nc == 0) return DYNMO_OK;
+  DYNMO_TIMED_LAUNCH(K_PERMUTE_SCATTER, st,
+                     permute_scatter_kernel<<<dim3(nc), dim3(kChunkThreads), 0, st>>>(expert_idx, n_slots, d->E,
+                                                                                      chunk_counts, src_slot, dst_pos));
+  if (d->k <= 2) return launch_rows<2>(d, x, dst_pos, x_p, st);
+  if (d->k <= 8) return launch_rows<8>(d, x, dst_pos, x_p, st);
+  return launch_rows<kMaxExperts>(d, x, dst_pos, x_p, st);
 }
 
 extern "C" int32_t dynmo_permute_bwd(const dynmo_desc* d, const void* dx_p, const int32_t* dst_pos, const void* dbase,
@@ -231,14 +246,6 @@ extern "C" int32_t dynmo_permute_bwd(const dynmo_desc* d, const void* dx_p, cons
   if (!dx_p || !dst_pos || !dx) return DYNMO_EINVAL;
   if (d->T == 0) return DYNMO_OK;
   hipStream_t st = (hipStream_t)stream;
-  const int row_vecs = (int)((size_t)d->H * elem_bytes(d->dtype) / 16);
-  const unsigned blocks = (unsigned)(((int64_t)d->T * 64 + 255) / 256);
-  if (d->dtype == DYNMO_BF16)
-    permute_bwd_kernel<bf16_t><<<dim3(blocks), dim3(256), 0, st>>>((const u32x4*)dx_p, dst_pos, (const u32x4*)dbase,
-                                                                   (u32x4*)dx, d->T, d->k, row_vecs);
-  else
-    permute_bwd_kernel<float><<<dim3(blocks), dim3(256), 0, st>>>((const u32x4*)dx_p, dst_pos, (const u32x4*)dbase,
-                                                                  (u32x4*)dx, d->T, d->k, row_vecs);
-  DYNMO_LAUNCH_CHECK();
-  return DYNMO_OK;
+  return d->dtype == DYNMO_BF16 ? launch_permute_bwd<bf16_t>(d, dx_p, dst_pos, dbase, dx, st)
+                                : launch_permute_bwd<float>(d, dx_p, dst_pos, dbase, dx, st);
 }
