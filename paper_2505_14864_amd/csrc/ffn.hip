@@ -34,6 +34,8 @@ extern "C" int32_t dynmo_grouped_ffn_fwd(const dynmo_desc* d, const void* x_p, c
   if (workspace_bytes < dynmo_grouped_ffn_fwd_workspace_bytes(d)) return DYNMO_EWORKSPACE;
   if (max_m_tiles(d, 64) > 65535) return DYNMO_EUNSUPPORTED;
   void* A = (void*)align_up((size_t)workspace, 256);
+  if (ffn_mfma_supported(d))
+    return ffn_fwd_mfma(d, x_p, seg_offsets, Wg, Wu, Wd, y_p, G_save, U_save, A, (hipStream_t)stream);
   return ffn_fwd_generic(d, x_p, seg_offsets, Wg, Wu, Wd, y_p, G_save, U_save, A, (hipStream_t)stream);
 }
 
@@ -52,6 +54,9 @@ extern "C" int32_t dynmo_grouped_ffn_bwd(const dynmo_desc* d, const void* dy_p, 
   void* dG = base;
   void* dU = base + act_bytes(d);
   void* A = base + 2 * act_bytes(d);
+  if (ffn_mfma_supported(d))
+    return ffn_bwd_mfma(d, dy_p, x_p, G_save, U_save, seg_offsets, Wg, Wu, Wd, dx_p, dWg, dWu, dWd, dG, dU, A,
+                        (hipStream_t)stream);
   return ffn_bwd_generic(d, dy_p, x_p, G_save, U_save, seg_offsets, Wg, Wu, Wd, dx_p, dWg, dWu, dWd, dG, dU, A,
                          (hipStream_t)stream);
 }

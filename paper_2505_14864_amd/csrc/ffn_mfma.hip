@@ -1,0 +1,473 @@
+// Grouped SwiGLU FFN on the gfx950 matrix cores (bf16 in, fp32 accumulate).
+//
+// One kernel template covers the five products of the layer:
+//   GATEUP  G = X Wg^T, U = X Wu^T, A = silu(G) U      (A, B both K-contiguous)
+//   DOWN    Y = A Wd^T                                  (A, B both K-contiguous)
+//   DA      dA = dY Wd  -> A, dG, dU                    (B stored [K][N])
+//   DX      dX = dG Wg + dU Wu                          (B stored [K][N], two K phases)
+//   DW      dW[e] = P_e^T Q_e over the rows of expert e (A, B both stored [K][M/N])
+//
+// Tiling: a 256x256 output tile per workgroup of four wavefronts (2x2, 128x128
+// each, as 4x4 v_mfma_f32_32x32x16_bf16 blocks = 256 accumulator registers per
+// lane), K in steps of 64 through two LDS stages.  Tiles whose memory layout has
+// K contiguous are kept [row][k] in LDS (row pitch 144 B, conflict-free 16-byte
+// fragment reads); tiles whose memory layout has the row index contiguous are
+// kept [k][row] (pitch 576 B) and read with ds_read_b64_tr_b16, which hands each
+// lane four consecutive k of one row -- so no operand is ever transposed in
+// HBM or by scalar LDS traffic.
+//
+// Ragged rows: the row-tile list is derived on the device from seg_offsets, so
+// no host synchronisation is needed; the grid is sized for the worst case and
+// surplus workgroups exit.  Workgroup ids are remapped so that each XCD (ids
+// congruent modulo 8) works on one contiguous run of tiles, ordered so that
+// neighbours share operand tiles in that XCD's L2.
+#include "common.h"
+#include "ffn.h"
+#include "profile.h"
+
+namespace dynmo {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((ext_vector_type(8))) short s16x8_t;
+
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int kMfmaThreads = 256;
+constexpr int kPitchK = 144;                 // bytes per row of a [row][k] tile: 64 bf16 + 16 pad
+constexpr int kPitchT = 576;                 // bytes per k-row of a [k][row] tile: 256 bf16 + 64 pad
+constexpr int kTileBytes = 256 * kPitchK;    // == 64 * kPitchT == 36864
+constexpr int kLdsBytes = 4 * kTileBytes;    // two stages of (A, B)
+constexpr int kXcds = 8;
+constexpr int kGroupN = 8;                   // column tiles that run side by side in one XCD
+
+static_assert(256 * kPitchK == 64 * kPitchT, "both tile layouts must have the same size");
+
+enum { MODE_GATEUP = 0, MODE_DOWN = 1, MODE_DA = 2, MODE_DX = 3, MODE_DW = 4 };
+
+struct GemmParams {
+  const int32_t* seg;
+  int E;
+  int M;  // rows of the output (MODE_DW only; the other modes take rows from seg)
+  int N;  // columns of the output (for GATEUP: F, and a tile spans 128 of them twice)
+  int K;  // contraction length per phase (MODE_DW: taken from seg)
+  const bf16_t* A1;
+  const bf16_t* A2;
+  long lda;
+  const bf16_t* B1;
+  const bf16_t* B2;
+  long ldb;
+  long b_expert_stride;
+  bf16_t* C0;
+  bf16_t* C1;
+  bf16_t* C2;
+  long ldc;
+  const bf16_t* G;
+  const bf16_t* U;
+};
+
+// ---- global -> registers -> LDS staging ---------------------------------------
+// A staged tile is 256 "rows" x 64 k.  Each thread moves eight 16-byte pieces.
+
+// [row][k] memory: element (row, k) at base + row*ld + k
+__device__ __forceinline__ void gload_rowk(u32x4 (&r)[8], const bf16_t* __restrict__ base, long ld, int row0, int row_end,
+                                           int k0, int k_end) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int c = tid + kMfmaThreads * j;
+    const int row = row0 + (c >> 3), k = k0 + (c & 7) * 8;
+    u32x4 v = {0, 0, 0, 0};
+    if (row < row_end && k < k_end) v = *(const u32x4*)(base + (long)row * ld + k);
+    r[j] = v;
+  }
+}
+
+// Same, but rows 0..127 of the tile come from base_lo and rows 128..255 from base_hi
+// (the gate and up weight rows that belong to the same output columns).
+__device__ __forceinline__ void gload_rowk_dual(u32x4 (&r)[8], const bf16_t* __restrict__ base_lo,
+                                                const bf16_t* __restrict__ base_hi, long ld, int row0, int row_end, int k0,
+                                                int k_end) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int c = tid + kMfmaThreads * j;
+    const int row = row0 + ((c >> 3) & 127), k = k0 + (c & 7) * 8;
+    const bf16_t* base = j < 4 ? base_lo : base_hi;
+    u32x4 v = {0, 0, 0, 0};
+    if (row < row_end && k < k_end) v = *(const u32x4*)(base + (long)row * ld + k);
+    r[j] = v;
+  }
+}
+
+// [k][row] memory: element (row, k) at base + k*ld + row
+__device__ __forceinline__ void gload_krow(u32x4 (&r)[8], const bf16_t* __restrict__ base, long ld, int row0, int row_end,
+                                           int k0, int k_end) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int c = tid + kMfmaThreads * j;
+    const int k = k0 + (c >> 5), row = row0 + (c & 31) * 8;
+    u32x4 v = {0, 0, 0, 0};
+    if (row < row_end && k < k_end) v = *(const u32x4*)(base + (long)k * ld + row);
+    r[j] = v;
+  }
+}
+
+template <bool TRANS>
+__device__ __forceinline__ void lstore(char* tile, const u32x4 (&r)[8]) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int c = tid + kMfmaThreads * j;
+    if (!TRANS)
+      *(u32x4*)(tile + (c >> 3) * kPitchK + (c & 7) * 16) = r[j];
+    else
+      *(u32x4*)(tile + (c >> 5) * kPitchT + (c & 31) * 16) = r[j];
+  }
+}
+
+// ---- LDS -> MFMA operand fragments ---------------------------------------------
+// Operand of v_mfma_f32_32x32x16_bf16: lane l holds, for row (l % 32) of the 32-row
+// block, the eight k values (l / 32) * 8 .. + 7 of the 16-wide k step.
+template <bool TRANS>
+__device__ __forceinline__ bf16x8_t lfrag(const char* tile, int blk, int ks) {
+  const int lane = threadIdx.x & 63;
+  if (!TRANS) {
+    const int off = (blk * 32 + (lane & 31)) * kPitchK + ks * 32 + (lane >> 5) * 16;
+    return *(const bf16x8_t*)(tile + off);
+  } else {
+    // ds_read_b64_tr_b16 works on groups of 16 lanes: lane s of a group points at
+    // four consecutive rows (s % 4) * 4 .. + 3 of k-row (s / 4); afterwards lane i
+    // of the group holds row i for those four k-rows.
+    const int s = lane & 15;
+    const int col = blk * 32 + ((lane >> 4) & 1) * 16 + (s & 3) * 4;
+    const int k = ks * 16 + (lane >> 5) * 8 + (s >> 2);
+    typedef __attribute__((address_space(3))) s16x4_t* lds_ptr;
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(tile + k * kPitchT + col * 2));
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(tile + (k + 4) * kPitchT + col * 2));
+    s16x8_t v;
+    v.s0 = lo.x; v.s1 = lo.y; v.s2 = lo.z; v.s3 = lo.w;
+    v.s4 = hi.x; v.s5 = hi.y; v.s6 = hi.z; v.s7 = hi.w;
+    return __builtin_bit_cast(bf16x8_t, v);
+  }
+}
+
+// ---- tile schedule ---------------------------------------------------------------
+struct Tile {
+  int e;       // expert
+  int m0;      // first output row (absolute row for the segmented modes)
+  int m_end;   // end of valid rows
+  int n0;      // first output column
+};
+
+// Segmented modes.  Tiles of one expert form a block; inside it column tiles go in
+// groups of kGroupN and row tiles vary fastest inside a group... see file header.
+__device__ __forceinline__ bool schedule_segmented(const int32_t* __restrict__ seg, int E, int n_tiles, int bn, Tile* t) {
+  int total = 0;
+  for (int e = 0; e < E; ++e) total += ((seg[e + 1] - seg[e] + BM - 1) / BM) * n_tiles;
+  const int per_xcd = (total + kXcds - 1) / kXcds;
+  const int xcd = blockIdx.x % kXcds, i = blockIdx.x / kXcds;
+  const int logical = xcd * per_xcd + i;
+  if (i >= per_xcd || logical >= total) return false;
+  int first = 0;
+  for (int e = 0; e < E; ++e) {
+    const int begin = seg[e], end = seg[e + 1];
+    const int mt = (end - begin + BM - 1) / BM;
+    const int tiles = mt * n_tiles;
+    if (logical < first + tiles) {
+      const int r = logical - first;
+      const int group = r / (mt * kGroupN);
+      const int within = r - group * (mt * kGroupN);
+      const int gn = min(kGroupN, n_tiles - group * kGroupN);
+      const int mi = within / gn, ni = group * kGroupN + within % gn;
+      t->e = e;
+      t->m0 = begin + mi * BM;
+      t->m_end = end;
+      t->n0 = ni * bn;
+      return true;
+    }
+    first += tiles;
+  }
+  return false;
+}
+
+// MODE_DW: every expert has the same (M/BM) x (N/BN) grid of output tiles.
+__device__ __forceinline__ bool schedule_dw(int E, int M, int N, Tile* t) {
+  const int mt = (M + BM - 1) / BM, nt = (N + BN - 1) / BN;
+  const int total = E * mt * nt;
+  const int per_xcd = (total + kXcds - 1) / kXcds;
+  const int xcd = blockIdx.x % kXcds, i = blockIdx.x / kXcds;
+  const int logical = xcd * per_xcd + i;
+  if (i >= per_xcd || logical >= total) return false;
+  const int e = logical / (mt * nt), r = logical % (mt * nt);
+  const int group = r / (mt * kGroupN);
+  const int within = r - group * (mt * kGroupN);
+  const int gn = min(kGroupN, nt - group * kGroupN);
+  t->e = e;
+  t->m0 = (within / gn) * BM;
+  t->m_end = M;
+  t->n0 = (group * kGroupN + within % gn) * BN;
+  return true;
+}
+
+__device__ __forceinline__ float silu_mul(float g, float u) { return g * sigmoidf_(g) * u; }
+
+template <int MODE>
+__global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmParams p) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  constexpr bool A_TRANS = MODE == MODE_DW;
+  constexpr bool B_TRANS = MODE == MODE_DA || MODE == MODE_DX || MODE == MODE_DW;
+  constexpr int TILE_N = MODE == MODE_GATEUP ? 128 : BN;  // output columns per tile
+
+  Tile t;
+  if (MODE == MODE_DW) {
+    if (!schedule_dw(p.E, p.M, p.N, &t)) return;
+  } else {
+    if (!schedule_segmented(p.seg, p.E, (p.N + TILE_N - 1) / TILE_N, TILE_N, &t)) return;
+  }
+
+  // contraction range and per-expert operand bases
+  int k_begin = 0, k_end = p.K;
+  if (MODE == MODE_DW) {
+    k_begin = p.seg[t.e];
+    k_end = p.seg[t.e + 1];
+  }
+  const bf16_t* B1 = p.B1 + (MODE == MODE_DW ? 0 : (long)t.e * p.b_expert_stride);
+  const bf16_t* B2 = (MODE == MODE_GATEUP || MODE == MODE_DX) ? p.B2 + (long)t.e * p.b_expert_stride : nullptr;
+  const int phases = MODE == MODE_DX ? 2 : 1;
+  const int kt_per_phase = (k_end - k_begin + BK - 1) / BK;
+  const int n_kt = kt_per_phase * phases;
+  const int n_end = p.N;
+
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  f32x16_t acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  u32x4 ra[8], rb[8];
+  auto fetch = [&](int kt) {
+    const int ph = MODE == MODE_DX ? kt / kt_per_phase : 0;
+    const int k0 = k_begin + (kt - ph * kt_per_phase) * BK;
+    const bf16_t* A = ph == 0 ? p.A1 : p.A2;
+    if (A_TRANS)
+      gload_krow(ra, A, p.lda, t.m0, t.m_end, k0, k_end);
+    else
+      gload_rowk(ra, A, p.lda, t.m0, t.m_end, k0, k_end);
+    if (MODE == MODE_GATEUP)
+      gload_rowk_dual(rb, B1, B2, p.ldb, t.n0, n_end, k0, k_end);
+    else if (B_TRANS)
+      gload_krow(rb, ph == 0 ? B1 : B2, p.ldb, t.n0, n_end, k0, k_end);
+    else
+      gload_rowk(rb, B1, p.ldb, t.n0, n_end, k0, k_end);
+  };
+  auto stash = [&](int stage) {
+    lstore<A_TRANS>(smem + (stage * 2) * kTileBytes, ra);
+    lstore<B_TRANS>(smem + (stage * 2 + 1) * kTileBytes, rb);
+  };
+
+  if (n_kt > 0) {
+    fetch(0);
+    stash(0);
+  }
+  __syncthreads();
+  for (int kt = 0; kt < n_kt; ++kt) {
+    const int stage = kt & 1;
+    if (kt + 1 < n_kt) fetch(kt + 1);
+    const char* As = smem + (stage * 2) * kTileBytes;
+    const char* Bs = As + kTileBytes;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8_t a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = lfrag<A_TRANS>(As, wm * 4 + i, ks);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int blk = MODE == MODE_GATEUP ? (j >> 1) * 4 + wn * 2 + (j & 1) : wn * 4 + j;
+        b[j] = lfrag<B_TRANS>(Bs, blk, ks);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < n_kt) stash(stage ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue.  Accumulator element r of block (i, j): row = i*32 + (r/4)*8 +
+  // (lane/32)*4 + r%4, column = lane % 32 of the block.
+  const int row_base = t.m0 + wm * 128 + (lane >> 5) * 4;
+  if (MODE == MODE_GATEUP) {
+    // blocks j = 0,1 hold G and j = 2,3 hold U for the same 64 columns
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int col = t.n0 + wn * 64 + j * 32 + (lane & 31);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = row_base + i * 32 + (r >> 2) * 8 + (r & 3);
+          if (row < t.m_end && col < n_end) {
+            const float g = acc[i][j][r], u = acc[i][j + 2][r];
+            const long o = (long)row * p.ldc + col;
+            p.C0[o] = f32_to_bf16(g);
+            p.C1[o] = f32_to_bf16(u);
+            p.C2[o] = f32_to_bf16(silu_mul(g, u));
+          }
+        }
+      }
+  } else {
+    bf16_t* C = p.C0 + (MODE == MODE_DW ? (long)t.e * p.M * p.N : 0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int col = t.n0 + wn * 128 + j * 32 + (lane & 31);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = row_base + i * 32 + (r >> 2) * 8 + (r & 3);
+          if (row < t.m_end && col < n_end) {
+            const long o = (long)row * p.ldc + col;
+            if (MODE == MODE_DA) {
+              float a_, dg, du;
+              swiglu_bwd(acc[i][j][r], bf16_to_f32(p.G[o]), bf16_to_f32(p.U[o]), &a_, &dg, &du);
+              p.C0[o] = f32_to_bf16(dg);
+              p.C1[o] = f32_to_bf16(du);
+              p.C2[o] = f32_to_bf16(a_);
+            } else {
+              C[o] = f32_to_bf16(acc[i][j][r]);
+            }
+          }
+        }
+      }
+  }
+}
+
+template <int MODE>
+static int32_t launch_mfma(const GemmParams& p, int blocks, KernelId id, hipStream_t st) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    DYNMO_HIP_TRY(hipFuncSetAttribute((const void*)ffn_mfma_kernel<MODE>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      kLdsBytes));
+    attr_set = true;
+  }
+  if (blocks <= 0) return DYNMO_OK;
+  blocks = (blocks + kXcds - 1) / kXcds * kXcds;
+  DYNMO_TIMED_LAUNCH(id, st, ffn_mfma_kernel<MODE><<<dim3(blocks), dim3(kMfmaThreads), kLdsBytes, st>>>(p));
+  return DYNMO_OK;
+}
+
+bool ffn_mfma_supported(const dynmo_desc* d) {
+  return d->dtype == DYNMO_BF16 && d->H % 8 == 0 && d->F % 8 == 0 &&
+         (int64_t)max_m_tiles(d, BM) * ((d->F + 127) / 128) < (1 << 30);
+}
+
+int32_t ffn_fwd_mfma(const dynmo_desc* d, const void* x_p, const int32_t* seg, const void* Wg, const void* Wu,
+                     const void* Wd, void* y_p, void* G, void* U, void* A, hipStream_t st) {
+  const int mt = max_m_tiles(d, BM);
+  const long FH = (long)d->F * d->H;
+  GemmParams p = {};
+  p.seg = seg;
+  p.E = d->E;
+  // G, U, A = gate/up projections
+  p.N = d->F;
+  p.K = d->H;
+  p.A1 = (const bf16_t*)x_p;
+  p.lda = d->H;
+  p.B1 = (const bf16_t*)Wg;
+  p.B2 = (const bf16_t*)Wu;
+  p.ldb = d->H;
+  p.b_expert_stride = FH;
+  p.C0 = (bf16_t*)G;
+  p.C1 = (bf16_t*)U;
+  p.C2 = (bf16_t*)A;
+  p.ldc = d->F;
+  int32_t rc = launch_mfma<MODE_GATEUP>(p, mt * ((d->F + 127) / 128), K_FFN_GATEUP, st);
+  if (rc) return rc;
+  // Y = A Wd^T
+  GemmParams q = {};
+  q.seg = seg;
+  q.E = d->E;
+  q.N = d->H;
+  q.K = d->F;
+  q.A1 = (const bf16_t*)A;
+  q.lda = d->F;
+  q.B1 = (const bf16_t*)Wd;
+  q.ldb = d->F;
+  q.b_expert_stride = FH;
+  q.C0 = (bf16_t*)y_p;
+  q.ldc = d->H;
+  return launch_mfma<MODE_DOWN>(q, mt * ((d->H + BN - 1) / BN), K_FFN_DOWN, st);
+}
+
+int32_t ffn_bwd_mfma(const dynmo_desc* d, const void* dy_p, const void* x_p, const void* G, const void* U,
+                     const int32_t* seg, const void* Wg, const void* Wu, const void* Wd, void* dx_p, void* dWg,
+                     void* dWu, void* dWd, void* dG, void* dU, void* A, hipStream_t st) {
+  const int mt = max_m_tiles(d, BM);
+  const long FH = (long)d->F * d->H;
+  const int tH = (d->H + BN - 1) / BN, tF = (d->F + BN - 1) / BN;
+  int32_t rc;
+  {  // dA = dY Wd, epilogue -> A, dG, dU
+    GemmParams p = {};
+    p.seg = seg;
+    p.E = d->E;
+    p.N = d->F;
+    p.K = d->H;
+    p.A1 = (const bf16_t*)dy_p;
+    p.lda = d->H;
+    p.B1 = (const bf16_t*)Wd;  // [H][F]: k = h rows, n = f contiguous
+    p.ldb = d->F;
+    p.b_expert_stride = FH;
+    p.C0 = (bf16_t*)dG;
+    p.C1 = (bf16_t*)dU;
+    p.C2 = (bf16_t*)A;
+    p.ldc = d->F;
+    p.G = (const bf16_t*)G;
+    p.U = (const bf16_t*)U;
+    if ((rc = launch_mfma<MODE_DA>(p, mt * tF, K_FFN_DA, st))) return rc;
+  }
+  {  // dX = dG Wg + dU Wu
+    GemmParams p = {};
+    p.seg = seg;
+    p.E = d->E;
+    p.N = d->H;
+    p.K = d->F;
+    p.A1 = (const bf16_t*)dG;
+    p.A2 = (const bf16_t*)dU;
+    p.lda = d->F;
+    p.B1 = (const bf16_t*)Wg;  // [F][H]: k = f rows, n = h contiguous
+    p.B2 = (const bf16_t*)Wu;
+    p.ldb = d->H;
+    p.b_expert_stride = FH;
+    p.C0 = (bf16_t*)dx_p;
+    p.ldc = d->H;
+    if ((rc = launch_mfma<MODE_DX>(p, mt * tH, K_FFN_DX, st))) return rc;
+  }
+  // weight gradients: contraction over the rows of each expert
+  auto dw = [&](const void* P, int M, const void* Q, int N, void* out, KernelId id) -> int32_t {
+    GemmParams p = {};
+    p.seg = seg;
+    p.E = d->E;
+    p.M = M;
+    p.N = N;
+    p.A1 = (const bf16_t*)P;
+    p.lda = M;
+    p.B1 = (const bf16_t*)Q;
+    p.ldb = N;
+    p.C0 = (bf16_t*)out;
+    p.ldc = N;
+    return launch_mfma<MODE_DW>(p, d->E * ((M + BM - 1) / BM) * ((N + BN - 1) / BN), id, st);
+  };
+  if ((rc = dw(dy_p, d->H, A, d->F, dWd, K_FFN_DWD))) return rc;
+  if ((rc = dw(dG, d->F, x_p, d->H, dWg, K_FFN_DWG))) return rc;
+  return dw(dU, d->F, x_p, d->H, dWu, K_FFN_DWU);
+}
+
+}  // namespace dynmo
