@@ -38,10 +38,13 @@ constexpr int kPitchK = 144;                 // bytes per row of a [row][k] tile
 constexpr int kPitchT = 576;                 // bytes per k-row of a [k][row] tile: 256 bf16 + 64 pad
 constexpr int kTileBytes = 256 * kPitchK;    // == 64 * kPitchT == 36864
 constexpr int kLdsBytes = 4 * kTileBytes;    // two stages of (A, B)
+constexpr int kEpPitch = 136;                // floats per row of an epilogue LDS patch (128 + 8 pad)
+constexpr int kEpWaveBytes = 32 * kEpPitch * 4;  // one 32-row band per wavefront
 constexpr int kXcds = 8;
 constexpr int kGroupN = 8;                   // column tiles that run side by side in one XCD
 
 static_assert(256 * kPitchK == 64 * kPitchT, "both tile layouts must have the same size");
+static_assert(4 * kEpWaveBytes <= kLdsBytes, "epilogue patches must fit in the staging buffers");
 
 enum { MODE_GATEUP = 0, MODE_DOWN = 1, MODE_DA = 2, MODE_DX = 3, MODE_DW = 4 };
 
@@ -67,50 +70,61 @@ struct GemmParams {
 };
 
 // ---- global -> registers -> LDS staging ---------------------------------------
-// A staged tile is 256 "rows" x 64 k.  Each thread moves eight 16-byte pieces.
+// A staged tile is 256 "rows" x 64 k.  Each thread moves eight 16-byte pieces with
+// raw buffer loads: a piece outside the valid rows / k range is given an offset
+// beyond the buffer's record count, for which the hardware returns zeros, so the
+// loads are branch-free.  Every offset that is not masked this way lies inside the
+// operand.  The buffer base already points at the tile's (row0, k0) element.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+constexpr uint32_t kOob = 0x80000000u;
 
-// [row][k] memory: element (row, k) at base + row*ld + k
-__device__ __forceinline__ void gload_rowk(u32x4 (&r)[8], const bf16_t* __restrict__ base, long ld, int row0, int row_end,
-                                           int k0, int k_end) {
+__device__ __forceinline__ rsrc_t make_rsrc(const bf16_t* p) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(p), 0, 0x7ffffffe, 0x00020000);
+}
+
+__device__ __forceinline__ u32x4 bload(rsrc_t rs, uint32_t off) {
+  return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0));
+}
+
+// [row][k] memory: piece j of a thread is row tid/8 + 32 j, k offset (tid%8)*8
+__device__ __forceinline__ void gload_rowk(u32x4 (&r)[8], rsrc_t rs, uint32_t ld_bytes, int rows_left, int k_left) {
   const int tid = threadIdx.x;
+  const int r0 = tid >> 3, kc = (tid & 7) * 8;
+  const uint32_t base = (uint32_t)r0 * ld_bytes + kc * 2;
+  const bool kv = kc < k_left;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    const int c = tid + kMfmaThreads * j;
-    const int row = row0 + (c >> 3), k = k0 + (c & 7) * 8;
-    u32x4 v = {0, 0, 0, 0};
-    if (row < row_end && k < k_end) v = *(const u32x4*)(base + (long)row * ld + k);
-    r[j] = v;
+    const bool v = kv && (r0 + 32 * j < rows_left);
+    r[j] = bload(rs, v ? base + (uint32_t)(32 * j) * ld_bytes : kOob);
   }
 }
 
-// Same, but rows 0..127 of the tile come from base_lo and rows 128..255 from base_hi
+// Same, but rows 0..127 of the tile come from rs_lo and rows 128..255 from rs_hi
 // (the gate and up weight rows that belong to the same output columns).
-__device__ __forceinline__ void gload_rowk_dual(u32x4 (&r)[8], const bf16_t* __restrict__ base_lo,
-                                                const bf16_t* __restrict__ base_hi, long ld, int row0, int row_end, int k0,
-                                                int k_end) {
+__device__ __forceinline__ void gload_rowk_dual(u32x4 (&r)[8], rsrc_t rs_lo, rsrc_t rs_hi, uint32_t ld_bytes,
+                                                int rows_left, int k_left) {
   const int tid = threadIdx.x;
+  const int r0 = tid >> 3, kc = (tid & 7) * 8;
+  const uint32_t base = (uint32_t)r0 * ld_bytes + kc * 2;
+  const bool kv = kc < k_left;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    const int c = tid + kMfmaThreads * j;
-    const int row = row0 + ((c >> 3) & 127), k = k0 + (c & 7) * 8;
-    const bf16_t* base = j < 4 ? base_lo : base_hi;
-    u32x4 v = {0, 0, 0, 0};
-    if (row < row_end && k < k_end) v = *(const u32x4*)(base + (long)row * ld + k);
-    r[j] = v;
+    const int jj = j & 3;
+    const bool v = kv && (r0 + 32 * jj < rows_left);
+    r[j] = bload(j < 4 ? rs_lo : rs_hi, v ? base + (uint32_t)(32 * jj) * ld_bytes : kOob);
   }
 }
 
-// [k][row] memory: element (row, k) at base + k*ld + row
-__device__ __forceinline__ void gload_krow(u32x4 (&r)[8], const bf16_t* __restrict__ base, long ld, int row0, int row_end,
-                                           int k0, int k_end) {
+// [k][row] memory: piece j of a thread is k-row tid/32 + 8 j, row offset (tid%32)*8
+__device__ __forceinline__ void gload_krow(u32x4 (&r)[8], rsrc_t rs, uint32_t ld_bytes, int rows_left, int k_left) {
   const int tid = threadIdx.x;
+  const int k0 = tid >> 5, rc = (tid & 31) * 8;
+  const uint32_t base = (uint32_t)k0 * ld_bytes + rc * 2;
+  const bool rv = rc < rows_left;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    const int c = tid + kMfmaThreads * j;
-    const int k = k0 + (c >> 5), row = row0 + (c & 31) * 8;
-    u32x4 v = {0, 0, 0, 0};
-    if (row < row_end && k < k_end) v = *(const u32x4*)(base + (long)k * ld + row);
-    r[j] = v;
+    const bool v = rv && (k0 + 8 * j < k_left);
+    r[j] = bload(rs, v ? base + (uint32_t)(8 * j) * ld_bytes : kOob);
   }
 }
 
@@ -252,20 +266,23 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   u32x4 ra[8], rb[8];
+  const uint32_t lda_b = (uint32_t)p.lda * 2, ldb_b = (uint32_t)p.ldb * 2;
   auto fetch = [&](int kt) {
     const int ph = MODE == MODE_DX ? kt / kt_per_phase : 0;
     const int k0 = k_begin + (kt - ph * kt_per_phase) * BK;
+    const int k_left = k_end - k0;
     const bf16_t* A = ph == 0 ? p.A1 : p.A2;
     if (A_TRANS)
-      gload_krow(ra, A, p.lda, t.m0, t.m_end, k0, k_end);
+      gload_krow(ra, make_rsrc(A + (long)k0 * p.lda + t.m0), lda_b, t.m_end - t.m0, k_left);
     else
-      gload_rowk(ra, A, p.lda, t.m0, t.m_end, k0, k_end);
+      gload_rowk(ra, make_rsrc(A + (long)t.m0 * p.lda + k0), lda_b, t.m_end - t.m0, k_left);
     if (MODE == MODE_GATEUP)
-      gload_rowk_dual(rb, B1, B2, p.ldb, t.n0, n_end, k0, k_end);
+      gload_rowk_dual(rb, make_rsrc(B1 + (long)t.n0 * p.ldb + k0), make_rsrc(B2 + (long)t.n0 * p.ldb + k0), ldb_b,
+                      n_end - t.n0, k_left);
     else if (B_TRANS)
-      gload_krow(rb, ph == 0 ? B1 : B2, p.ldb, t.n0, n_end, k0, k_end);
+      gload_krow(rb, make_rsrc((ph == 0 ? B1 : B2) + (long)k0 * p.ldb + t.n0), ldb_b, n_end - t.n0, k_left);
     else
-      gload_rowk(rb, B1, p.ldb, t.n0, n_end, k0, k_end);
+      gload_rowk(rb, make_rsrc(B1 + (long)t.n0 * p.ldb + k0), ldb_b, n_end - t.n0, k_left);
   };
   auto stash = [&](int stage) {
     lstore<A_TRANS>(smem + (stage * 2) * kTileBytes, ra);
@@ -301,52 +318,72 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     __syncthreads();
   }
 
-  // ---- epilogue.  Accumulator element r of block (i, j): row = i*32 + (r/4)*8 +
-  // (lane/32)*4 + r%4, column = lane % 32 of the block.
-  const int row_base = t.m0 + wm * 128 + (lane >> 5) * 4;
-  if (MODE == MODE_GATEUP) {
-    // blocks j = 0,1 hold G and j = 2,3 hold U for the same 64 columns
+  // ---- epilogue.  Accumulator element r of block (i, j) is row i*32 + (r/4)*8 +
+  // (lane/32)*4 + r%4, column j*32 + lane%32 of the wavefront's 128x128 part.  Each
+  // wavefront passes one 32-row band at a time through its own LDS patch (fp32,
+  // padded rows) so that global memory sees 16-byte accesses along rows.
+  float* ep = (float*)(smem + wave * kEpWaveBytes);
+  const bf16_t* __restrict__ Gs = p.G;
+  const bf16_t* __restrict__ Us = p.U;
+  bf16_t* __restrict__ C0 = p.C0 + (MODE == MODE_DW ? (long)t.e * p.M * p.N : 0);
+  bf16_t* __restrict__ C1 = p.C1;
+  bf16_t* __restrict__ C2 = p.C2;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 4; ++i) {
+    if (i > 0) __syncthreads();
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int col = t.n0 + wn * 64 + j * 32 + (lane & 31);
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = row_base + i * 32 + (r >> 2) * 8 + (r & 3);
-          if (row < t.m_end && col < n_end) {
-            const float g = acc[i][j][r], u = acc[i][j + 2][r];
-            const long o = (long)row * p.ldc + col;
-            p.C0[o] = f32_to_bf16(g);
-            p.C1[o] = f32_to_bf16(u);
-            p.C2[o] = f32_to_bf16(silu_mul(g, u));
-          }
+      for (int r = 0; r < 16; ++r)
+        ep[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * kEpPitch + j * 32 + (lane & 31)] = acc[i][j][r];
+    __syncthreads();
+    const int band_row = t.m0 + wm * 128 + i * 32;
+    if (MODE == MODE_GATEUP) {
+      // LDS row: 64 gate columns then the 64 matching up columns
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const int rl = s * 8 + (lane >> 3), c0 = (lane & 7) * 8;
+        const int row = band_row + rl, col = t.n0 + wn * 64 + c0;
+        float g[8], u[8], a_[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          g[q] = ep[rl * kEpPitch + c0 + q];
+          u[q] = ep[rl * kEpPitch + 64 + c0 + q];
+          a_[q] = silu_mul(g[q], u[q]);
+        }
+        if (row < t.m_end && col < n_end) {
+          const long o = (long)row * p.ldc + col;
+          *(u32x4*)(C0 + o) = pack16<bf16_t>(g);
+          *(u32x4*)(C1 + o) = pack16<bf16_t>(u);
+          *(u32x4*)(C2 + o) = pack16<bf16_t>(a_);
         }
       }
-  } else {
-    bf16_t* C = p.C0 + (MODE == MODE_DW ? (long)t.e * p.M * p.N : 0);
+    } else {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+      for (int s = 0; s < 8; ++s) {
+        const int rl = s * 4 + (lane >> 4), c0 = (lane & 15) * 8;
+        const int row = band_row + rl, col = t.n0 + wn * 128 + c0;
+        const bool ok = row < t.m_end && col < n_end;
+        const long o = (long)row * p.ldc + col;
+        float v[8];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int col = t.n0 + wn * 128 + j * 32 + (lane & 31);
+        for (int q = 0; q < 8; ++q) v[q] = ep[rl * kEpPitch + c0 + q];
+        if (MODE == MODE_DA) {
+          if (ok) {
+            float g[8], u[8], a_[8], dg[8], du[8];
+            unpack16<bf16_t>(*(const u32x4*)(Gs + o), g);
+            unpack16<bf16_t>(*(const u32x4*)(Us + o), u);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = row_base + i * 32 + (r >> 2) * 8 + (r & 3);
-          if (row < t.m_end && col < n_end) {
-            const long o = (long)row * p.ldc + col;
-            if (MODE == MODE_DA) {
-              float a_, dg, du;
-              swiglu_bwd(acc[i][j][r], bf16_to_f32(p.G[o]), bf16_to_f32(p.U[o]), &a_, &dg, &du);
-              p.C0[o] = f32_to_bf16(dg);
-              p.C1[o] = f32_to_bf16(du);
-              p.C2[o] = f32_to_bf16(a_);
-            } else {
-              C[o] = f32_to_bf16(acc[i][j][r]);
-            }
+            for (int q = 0; q < 8; ++q) swiglu_bwd(v[q], g[q], u[q], &a_[q], &dg[q], &du[q]);
+            *(u32x4*)(C0 + o) = pack16<bf16_t>(dg);
+            *(u32x4*)(C1 + o) = pack16<bf16_t>(du);
+            *(u32x4*)(C2 + o) = pack16<bf16_t>(a_);
           }
+        } else if (ok) {
+          *(u32x4*)(C0 + o) = pack16<bf16_t>(v);
         }
       }
+    }
   }
 }
 
