@@ -21,6 +21,9 @@
 // surplus workgroups exit.  Workgroup ids are remapped so that each XCD (ids
 // congruent modulo 8) works on one contiguous run of tiles, ordered so that
 // neighbours share operand tiles in that XCD's L2.
+#include <type_traits>
+#include <utility>
+
 #include "common.h"
 #include "ffn.h"
 #include "profile.h"
@@ -86,59 +89,53 @@ __device__ __forceinline__ u32x4 bload(rsrc_t rs, uint32_t off) {
   return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0));
 }
 
-// [row][k] memory: piece j of a thread is row tid/8 + 32 j, k offset (tid%8)*8
-__device__ __forceinline__ void gload_rowk(u32x4 (&r)[8], rsrc_t rs, uint32_t ld_bytes, int rows_left, int k_left) {
-  const int tid = threadIdx.x;
-  const int r0 = tid >> 3, kc = (tid & 7) * 8;
-  const uint32_t base = (uint32_t)r0 * ld_bytes + kc * 2;
-  const bool kv = kc < k_left;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const bool v = kv && (r0 + 32 * j < rows_left);
-    r[j] = bload(rs, v ? base + (uint32_t)(32 * j) * ld_bytes : kOob);
-  }
-}
+// Per-thread offsets of the eight pieces of a staged tile.  Row validity does not
+// change along k, so it is folded into the offsets once per output tile; the k
+// validity is applied per k tile (it only bites in a ragged last tile).
+struct Pieces {
+  uint32_t off[8];  // byte offset from the tile's (row0, k0) element, or kOob
+  int kpos[8];      // k index of the piece inside the 64-wide k tile
+};
 
-// Same, but rows 0..127 of the tile come from rs_lo and rows 128..255 from rs_hi
-// (the gate and up weight rows that belong to the same output columns).
-__device__ __forceinline__ void gload_rowk_dual(u32x4 (&r)[8], rsrc_t rs_lo, rsrc_t rs_hi, uint32_t ld_bytes,
-                                                int rows_left, int k_left) {
+// [row][k] memory: piece j of a thread is row tid/8 + 32 j, k offset (tid%8)*8.
+// `wrap` = 128 for the gate/up pairing (pieces 4..7 repeat rows 0..127 of a second matrix).
+__device__ __forceinline__ Pieces pieces_rowk(uint32_t ld_bytes, int rows_left, int wrap) {
+  Pieces ps;
   const int tid = threadIdx.x;
   const int r0 = tid >> 3, kc = (tid & 7) * 8;
-  const uint32_t base = (uint32_t)r0 * ld_bytes + kc * 2;
-  const bool kv = kc < k_left;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    const int jj = j & 3;
-    const bool v = kv && (r0 + 32 * jj < rows_left);
-    r[j] = bload(j < 4 ? rs_lo : rs_hi, v ? base + (uint32_t)(32 * jj) * ld_bytes : kOob);
+    const int row = (r0 + 32 * j) % wrap;
+    ps.off[j] = row < rows_left ? (uint32_t)row * ld_bytes + kc * 2 : kOob;
+    ps.kpos[j] = kc;
   }
+  return ps;
 }
 
 // [k][row] memory: piece j of a thread is k-row tid/32 + 8 j, row offset (tid%32)*8
-__device__ __forceinline__ void gload_krow(u32x4 (&r)[8], rsrc_t rs, uint32_t ld_bytes, int rows_left, int k_left) {
+__device__ __forceinline__ Pieces pieces_krow(uint32_t ld_bytes, int rows_left) {
+  Pieces ps;
   const int tid = threadIdx.x;
   const int k0 = tid >> 5, rc = (tid & 31) * 8;
-  const uint32_t base = (uint32_t)k0 * ld_bytes + rc * 2;
-  const bool rv = rc < rows_left;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    const bool v = rv && (k0 + 8 * j < k_left);
-    r[j] = bload(rs, v ? base + (uint32_t)(8 * j) * ld_bytes : kOob);
+    ps.off[j] = rc < rows_left ? (uint32_t)(k0 + 8 * j) * ld_bytes + rc * 2 : kOob;
+    ps.kpos[j] = k0 + 8 * j;
   }
+  return ps;
+}
+
+__device__ __forceinline__ u32x4 load_piece(rsrc_t rs, const Pieces& ps, int j, int k_left) {
+  return bload(rs, ps.kpos[j] < k_left ? ps.off[j] : kOob);
 }
 
 template <bool TRANS>
-__device__ __forceinline__ void lstore(char* tile, const u32x4 (&r)[8]) {
-  const int tid = threadIdx.x;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int c = tid + kMfmaThreads * j;
-    if (!TRANS)
-      *(u32x4*)(tile + (c >> 3) * kPitchK + (c & 7) * 16) = r[j];
-    else
-      *(u32x4*)(tile + (c >> 5) * kPitchT + (c & 31) * 16) = r[j];
-  }
+__device__ __forceinline__ void store_piece(char* tile, const u32x4& v, int j) {
+  const int c = threadIdx.x + kMfmaThreads * j;
+  if (!TRANS)
+    *(u32x4*)(tile + (c >> 3) * kPitchK + (c & 7) * 16) = v;
+  else
+    *(u32x4*)(tile + (c >> 5) * kPitchT + (c & 31) * 16) = v;
 }
 
 // ---- LDS -> MFMA operand fragments ---------------------------------------------
@@ -225,6 +222,16 @@ __device__ __forceinline__ bool schedule_dw(int E, int M, int N, Tile* t) {
   return true;
 }
 
+template <int... Is, typename F>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>) {
+  (f(std::integral_constant<int, Is>{}), ...);
+}
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), fully unrolled
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 __device__ __forceinline__ float silu_mul(float g, float u) { return g * sigmoidf_(g) * u; }
 
 template <int MODE>
@@ -265,58 +272,126 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+  // ---- main loop -------------------------------------------------------------
+  // A hand-ordered software pipeline; __builtin_amdgcn_sched_barrier(0) after every
+  // MFMA slot keeps the compiler from regrouping it.  Tile kt is in LDS stage kt%2
+  // and registers ra/rb hold tile kt+1 on entry.  Each of the four 16-wide k steps
+  // issues 16 MFMAs on fragments that were read during the step before:
+  //   step 0: MFMAs | fragment reads for step 1
+  //   step 1: MFMAs | fragment reads for step 2
+  //   step 2: MFMAs | fragment reads for step 3, LDS writes of tile kt+1 (A), loads of tile kt+2 (A)
+  //   step 3: first 8 MFMAs | LDS writes of tile kt+1 (B), loads of tile kt+2 (B)
+  //           barrier; fragment reads for step 0 of tile kt+1; last 8 MFMAs
+  // so LDS latency is always covered by MFMAs in flight, and a global load has a
+  // whole tile of MFMA time to land before its LDS write.  Past the last tile the
+  // loads are masked (zeros, no memory access) and the LDS writes are harmless,
+  // which keeps the loop body free of branches.
   u32x4 ra[8], rb[8];
+  bf16x8_t fa[2][4], fb[2][4];
   const uint32_t lda_b = (uint32_t)p.lda * 2, ldb_b = (uint32_t)p.ldb * 2;
-  auto fetch = [&](int kt) {
-    const int ph = MODE == MODE_DX ? kt / kt_per_phase : 0;
-    const int k0 = k_begin + (kt - ph * kt_per_phase) * BK;
-    const int k_left = k_end - k0;
-    const bf16_t* A = ph == 0 ? p.A1 : p.A2;
-    if (A_TRANS)
-      gload_krow(ra, make_rsrc(A + (long)k0 * p.lda + t.m0), lda_b, t.m_end - t.m0, k_left);
-    else
-      gload_rowk(ra, make_rsrc(A + (long)t.m0 * p.lda + k0), lda_b, t.m_end - t.m0, k_left);
-    if (MODE == MODE_GATEUP)
-      gload_rowk_dual(rb, make_rsrc(B1 + (long)t.n0 * p.ldb + k0), make_rsrc(B2 + (long)t.n0 * p.ldb + k0), ldb_b,
-                      n_end - t.n0, k_left);
-    else if (B_TRANS)
-      gload_krow(rb, make_rsrc((ph == 0 ? B1 : B2) + (long)k0 * p.ldb + t.n0), ldb_b, n_end - t.n0, k_left);
-    else
-      gload_rowk(rb, make_rsrc(B1 + (long)t.n0 * p.ldb + k0), ldb_b, n_end - t.n0, k_left);
-  };
-  auto stash = [&](int stage) {
-    lstore<A_TRANS>(smem + (stage * 2) * kTileBytes, ra);
-    lstore<B_TRANS>(smem + (stage * 2 + 1) * kTileBytes, rb);
-  };
+  const Pieces pa = A_TRANS ? pieces_krow(lda_b, t.m_end - t.m0) : pieces_rowk(lda_b, t.m_end - t.m0, 256);
+  const Pieces pb = B_TRANS ? pieces_krow(ldb_b, n_end - t.n0)
+                            : pieces_rowk(ldb_b, n_end - t.n0, MODE == MODE_GATEUP ? 128 : 256);
 
-  if (n_kt > 0) {
-    fetch(0);
-    stash(0);
+  // operand bases of k tile kt (wave-uniform), and how many k are left in it
+  struct KTile {
+    rsrc_t a, b_lo, b_hi;
+    int k_left;
+  };
+  auto ktile = [&](int kt) {
+    int ph = MODE == MODE_DX ? kt / kt_per_phase : 0;
+    if (MODE == MODE_DX && ph > 1) ph = 1;
+    const int k0 = k_begin + (kt - ph * kt_per_phase) * BK;
+    KTile q;
+    q.k_left = kt < n_kt ? k_end - k0 : 0;
+    const bf16_t* A = ph == 0 ? p.A1 : p.A2;
+    const bf16_t* B = (MODE == MODE_DX && ph == 1) ? B2 : B1;
+    q.a = make_rsrc(A_TRANS ? A + (long)k0 * p.lda + t.m0 : A + (long)t.m0 * p.lda + k0);
+    q.b_lo = make_rsrc(B_TRANS ? B + (long)k0 * p.ldb + t.n0 : B + (long)t.n0 * p.ldb + k0);
+    q.b_hi = MODE == MODE_GATEUP ? make_rsrc(B2 + (long)t.n0 * p.ldb + k0) : q.b_lo;
+    return q;
+  };
+  auto load_a = [&](const KTile& q, int j) { ra[j] = load_piece(q.a, pa, j, q.k_left); };
+  auto load_b = [&](const KTile& q, int j) {
+    rb[j] = load_piece((MODE == MODE_GATEUP && j >= 4) ? q.b_hi : q.b_lo, pb, j, q.k_left);
+  };
+  // fragment f of a step: 0..3 = rows of A, 4..7 = columns of B
+  auto read_frag = [&](auto BUF, auto F, int stage, int ks) {
+    constexpr int Q = decltype(BUF)::value, f = decltype(F)::value;
+    const char* As = smem + (stage * 2) * kTileBytes;
+    if (f < 4) {
+      fa[Q][f & 3] = lfrag<A_TRANS>(As, wm * 4 + f, ks);
+    } else {
+      constexpr int j = f & 3;
+      const int blk = MODE == MODE_GATEUP ? (j >> 1) * 4 + wn * 2 + (j & 1) : wn * 4 + j;
+      fb[Q][j] = lfrag<B_TRANS>(As + kTileBytes, blk, ks);
+    }
+  };
+  auto mfma = [&](auto BUF, auto M) {
+    constexpr int Q = decltype(BUF)::value, i = decltype(M)::value >> 2, j = decltype(M)::value & 3;
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[Q][i], fb[Q][j], acc[i][j], 0, 0, 0);
+  };
+  const std::integral_constant<int, 0> c0;
+  const std::integral_constant<int, 1> c1;
+
+  {
+    const KTile q0 = ktile(0);
+    static_for<8>([&](auto J) { load_a(q0, J); });
+    static_for<8>([&](auto J) { load_b(q0, J); });
+    static_for<8>([&](auto J) { store_piece<A_TRANS>(smem, ra[J], J); });
+    static_for<8>([&](auto J) { store_piece<B_TRANS>(smem + kTileBytes, rb[J], J); });
+    const KTile q1 = ktile(1);
+    static_for<8>([&](auto J) { load_a(q1, J); });
+    static_for<8>([&](auto J) { load_b(q1, J); });
   }
   __syncthreads();
+  static_for<8>([&](auto F) { read_frag(c0, F, 0, 0); });
+
   for (int kt = 0; kt < n_kt; ++kt) {
     const int stage = kt & 1;
-    if (kt + 1 < n_kt) fetch(kt + 1);
-    const char* As = smem + (stage * 2) * kTileBytes;
-    const char* Bs = As + kTileBytes;
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8_t a[4], b[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) a[i] = lfrag<A_TRANS>(As, wm * 4 + i, ks);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int blk = MODE == MODE_GATEUP ? (j >> 1) * 4 + wn * 2 + (j & 1) : wn * 4 + j;
-        b[j] = lfrag<B_TRANS>(Bs, blk, ks);
+    char* next = smem + ((stage ^ 1) * 2) * kTileBytes;
+    const KTile q2 = ktile(kt + 2);
+    __builtin_amdgcn_sched_barrier(0);
+    // step 0: fragments of step 1 go to buffer 1
+    static_for<16>([&](auto M) {
+      if constexpr ((M & 1) == 0) read_frag(c1, std::integral_constant<int, M / 2>{}, stage, 1);
+      mfma(c0, M);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    // step 1
+    static_for<16>([&](auto M) {
+      if constexpr ((M & 1) == 0) read_frag(c0, std::integral_constant<int, M / 2>{}, stage, 2);
+      mfma(c1, M);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    // step 2: also move operand A of the next tile into LDS and refill its registers
+    static_for<16>([&](auto M) {
+      if constexpr ((M & 1) == 0) {
+        read_frag(c1, std::integral_constant<int, M / 2>{}, stage, 3);
+      } else {
+        store_piece<A_TRANS>(next, ra[M / 2], M / 2);
+        load_a(q2, M / 2);
       }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < n_kt) stash(stage ^ 1);
+      mfma(c0, M);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    // step 3, first half: operand B likewise
+    static_for<8>([&](auto M) {
+      store_piece<B_TRANS>(next + kTileBytes, rb[M], M);
+      load_b(q2, M);
+      mfma(c1, M);
+      __builtin_amdgcn_sched_barrier(0);
+    });
     __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+    // step 3, second half, with the next tile's first fragments in flight
+    static_for<8>([&](auto M) {
+      read_frag(c0, M, stage ^ 1, 0);
+      mfma(c1, std::integral_constant<int, M + 8>{});
+      __builtin_amdgcn_sched_barrier(0);
+    });
   }
+  __syncthreads();
 
   // ---- epilogue.  Accumulator element r of block (i, j) is row i*32 + (r/4)*8 +
   // (lane/32)*4 + r%4, column j*32 + lane%32 of the wavefront's 128x128 part.  Each
