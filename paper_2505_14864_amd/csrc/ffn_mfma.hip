@@ -7,9 +7,11 @@
 //   DX      dX = dG Wg + dU Wu                          (B stored [K][N], two K phases)
 //   DW      dW[e] = P_e^T Q_e over the rows of expert e (A, B both stored [K][M/N])
 //
-// Tiling: a 256x256 output tile per workgroup of four wavefronts (2x2, 128x128
-// each, as 4x4 v_mfma_f32_32x32x16_bf16 blocks = 256 accumulator registers per
-// lane), K in steps of 64 through two LDS stages.  Tiles whose memory layout has
+// Tiling: a 256x256 output tile per workgroup of eight wavefronts (4x2, 64x128
+// each, as 2x4 v_mfma_f32_32x32x16_bf16 blocks = 128 accumulator registers per
+// lane), K in steps of 64 through two LDS stages.  Two wavefronts share each SIMD:
+// one wavefront alone cannot issue MFMAs back to back (measured 87% of the MFMA
+// rate, against 99% with two).  Tiles whose memory layout has
 // K contiguous are kept [row][k] in LDS (row pitch 144 B, conflict-free 16-byte
 // fragment reads); tiles whose memory layout has the row index contiguous are
 // kept [k][row] (pitch 576 B) and read with ds_read_b64_tr_b16, which hands each
@@ -36,7 +38,8 @@ typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 typedef __attribute__((ext_vector_type(8))) short s16x8_t;
 
 constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int kMfmaThreads = 256;
+constexpr int kMfmaThreads = 512;              // eight wavefronts: two per SIMD
+constexpr int kPieces = 2048 / kMfmaThreads;   // 16-byte pieces of a staged tile per thread
 constexpr int kPitchK = 144;                 // bytes per row of a [row][k] tile: 64 bf16 + 16 pad
 constexpr int kPitchT = 576;                 // bytes per k-row of a [k][row] tile: 256 bf16 + 64 pad
 constexpr int kTileBytes = 256 * kPitchK;    // == 64 * kPitchT == 36864
@@ -47,7 +50,7 @@ constexpr int kXcds = 8;
 constexpr int kGroupN = 8;                   // column tiles that run side by side in one XCD
 
 static_assert(256 * kPitchK == 64 * kPitchT, "both tile layouts must have the same size");
-static_assert(4 * kEpWaveBytes <= kLdsBytes, "epilogue patches must fit in the staging buffers");
+static_assert((kMfmaThreads / 64) * kEpWaveBytes <= kLdsBytes, "epilogue patches must fit in the staging buffers");
 
 enum { MODE_GATEUP = 0, MODE_DOWN = 1, MODE_DA = 2, MODE_DX = 3, MODE_DW = 4 };
 
@@ -93,34 +96,34 @@ __device__ __forceinline__ u32x4 bload(rsrc_t rs, uint32_t off) {
 // change along k, so it is folded into the offsets once per output tile; the k
 // validity is applied per k tile (it only bites in a ragged last tile).
 struct Pieces {
-  uint32_t off[8];  // byte offset from the tile's (row0, k0) element, or kOob
-  int kpos[8];      // k index of the piece inside the 64-wide k tile
+  uint32_t off[kPieces];  // byte offset from the tile's (row0, k0) element, or kOob
+  int kpos[kPieces];      // k index of the piece inside the 64-wide k tile
 };
 
-// [row][k] memory: piece j of a thread is row tid/8 + 32 j, k offset (tid%8)*8.
+// [row][k] memory: piece j of a thread is row tid/8 + 64 j, k offset (tid%8)*8.
 // `wrap` = 128 for the gate/up pairing (pieces 4..7 repeat rows 0..127 of a second matrix).
 __device__ __forceinline__ Pieces pieces_rowk(uint32_t ld_bytes, int rows_left, int wrap) {
   Pieces ps;
   const int tid = threadIdx.x;
   const int r0 = tid >> 3, kc = (tid & 7) * 8;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int row = (r0 + 32 * j) % wrap;
+  for (int j = 0; j < kPieces; ++j) {
+    const int row = (r0 + (kMfmaThreads / 8) * j) % wrap;
     ps.off[j] = row < rows_left ? (uint32_t)row * ld_bytes + kc * 2 : kOob;
     ps.kpos[j] = kc;
   }
   return ps;
 }
 
-// [k][row] memory: piece j of a thread is k-row tid/32 + 8 j, row offset (tid%32)*8
+// [k][row] memory: piece j of a thread is k-row tid/32 + 16 j, row offset (tid%32)*8
 __device__ __forceinline__ Pieces pieces_krow(uint32_t ld_bytes, int rows_left) {
   Pieces ps;
   const int tid = threadIdx.x;
   const int k0 = tid >> 5, rc = (tid & 31) * 8;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    ps.off[j] = rc < rows_left ? (uint32_t)(k0 + 8 * j) * ld_bytes + rc * 2 : kOob;
-    ps.kpos[j] = k0 + 8 * j;
+  for (int j = 0; j < kPieces; ++j) {
+    ps.off[j] = rc < rows_left ? (uint32_t)(k0 + (kMfmaThreads / 32) * j) * ld_bytes + rc * 2 : kOob;
+    ps.kpos[j] = k0 + (kMfmaThreads / 32) * j;
   }
   return ps;
 }
@@ -262,11 +265,11 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   const int n_end = p.N;
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave >> 1, wn = wave & 1;  // 4 x 2 wavefronts, 64 x 128 outputs each
 
-  f32x16_t acc[4][4];
+  f32x16_t acc[2][4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -276,18 +279,18 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   // A hand-ordered software pipeline; __builtin_amdgcn_sched_barrier(0) after every
   // MFMA slot keeps the compiler from regrouping it.  Tile kt is in LDS stage kt%2
   // and registers ra/rb hold tile kt+1 on entry.  Each of the four 16-wide k steps
-  // issues 16 MFMAs on fragments that were read during the step before:
+  // issues 8 MFMAs on fragments that were read during the step before:
   //   step 0: MFMAs | fragment reads for step 1
   //   step 1: MFMAs | fragment reads for step 2
   //   step 2: MFMAs | fragment reads for step 3, LDS writes of tile kt+1 (A), loads of tile kt+2 (A)
-  //   step 3: first 8 MFMAs | LDS writes of tile kt+1 (B), loads of tile kt+2 (B)
-  //           barrier; fragment reads for step 0 of tile kt+1; last 8 MFMAs
-  // so LDS latency is always covered by MFMAs in flight, and a global load has a
-  // whole tile of MFMA time to land before its LDS write.  Past the last tile the
-  // loads are masked (zeros, no memory access) and the LDS writes are harmless,
-  // which keeps the loop body free of branches.
-  u32x4 ra[8], rb[8];
-  bf16x8_t fa[2][4], fb[2][4];
+  //   step 3: first 4 MFMAs | LDS writes of tile kt+1 (B), loads of tile kt+2 (B)
+  //           barrier; fragment reads for step 0 of tile kt+1; last 4 MFMAs
+  // so LDS latency is covered by MFMAs in flight (and by the SIMD's other
+  // wavefront), and a global load has a whole tile of MFMA time to land before its
+  // LDS write.  Past the last tile the loads are masked (zeros, no memory access)
+  // and the LDS writes are harmless, which keeps the loop body free of branches.
+  u32x4 ra[kPieces], rb[kPieces];
+  bf16x8_t fa[2][2], fb[2][4];
   const uint32_t lda_b = (uint32_t)p.lda * 2, ldb_b = (uint32_t)p.ldb * 2;
   const Pieces pa = A_TRANS ? pieces_krow(lda_b, t.m_end - t.m0) : pieces_rowk(lda_b, t.m_end - t.m0, 256);
   const Pieces pb = B_TRANS ? pieces_krow(ldb_b, n_end - t.n0)
@@ -313,16 +316,16 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   };
   auto load_a = [&](const KTile& q, int j) { ra[j] = load_piece(q.a, pa, j, q.k_left); };
   auto load_b = [&](const KTile& q, int j) {
-    rb[j] = load_piece((MODE == MODE_GATEUP && j >= 4) ? q.b_hi : q.b_lo, pb, j, q.k_left);
+    rb[j] = load_piece((MODE == MODE_GATEUP && j >= kPieces / 2) ? q.b_hi : q.b_lo, pb, j, q.k_left);
   };
-  // fragment f of a step: 0..3 = rows of A, 4..7 = columns of B
+  // fragment f of a step: 0..1 = row blocks of A, 2..5 = column blocks of B
   auto read_frag = [&](auto BUF, auto F, int stage, int ks) {
     constexpr int Q = decltype(BUF)::value, f = decltype(F)::value;
     const char* As = smem + (stage * 2) * kTileBytes;
-    if (f < 4) {
-      fa[Q][f & 3] = lfrag<A_TRANS>(As, wm * 4 + f, ks);
+    if constexpr (f < 2) {
+      fa[Q][f] = lfrag<A_TRANS>(As, wm * 2 + f, ks);
     } else {
-      constexpr int j = f & 3;
+      constexpr int j = f - 2;
       const int blk = MODE == MODE_GATEUP ? (j >> 1) * 4 + wn * 2 + (j & 1) : wn * 4 + j;
       fb[Q][j] = lfrag<B_TRANS>(As + kTileBytes, blk, ks);
     }
@@ -336,16 +339,16 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
 
   {
     const KTile q0 = ktile(0);
-    static_for<8>([&](auto J) { load_a(q0, J); });
-    static_for<8>([&](auto J) { load_b(q0, J); });
-    static_for<8>([&](auto J) { store_piece<A_TRANS>(smem, ra[J], J); });
-    static_for<8>([&](auto J) { store_piece<B_TRANS>(smem + kTileBytes, rb[J], J); });
+    static_for<kPieces>([&](auto J) { load_a(q0, J); });
+    static_for<kPieces>([&](auto J) { load_b(q0, J); });
+    static_for<kPieces>([&](auto J) { store_piece<A_TRANS>(smem, ra[J], J); });
+    static_for<kPieces>([&](auto J) { store_piece<B_TRANS>(smem + kTileBytes, rb[J], J); });
     const KTile q1 = ktile(1);
-    static_for<8>([&](auto J) { load_a(q1, J); });
-    static_for<8>([&](auto J) { load_b(q1, J); });
+    static_for<kPieces>([&](auto J) { load_a(q1, J); });
+    static_for<kPieces>([&](auto J) { load_b(q1, J); });
   }
   __syncthreads();
-  static_for<8>([&](auto F) { read_frag(c0, F, 0, 0); });
+  static_for<6>([&](auto F) { read_frag(c0, F, 0, 0); });
 
   for (int kt = 0; kt < n_kt; ++kt) {
     const int stage = kt & 1;
@@ -353,22 +356,21 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     const KTile q2 = ktile(kt + 2);
     __builtin_amdgcn_sched_barrier(0);
     // step 0: fragments of step 1 go to buffer 1
-    static_for<16>([&](auto M) {
-      if constexpr ((M & 1) == 0) read_frag(c1, std::integral_constant<int, M / 2>{}, stage, 1);
+    static_for<8>([&](auto M) {
+      if constexpr (M < 6) read_frag(c1, M, stage, 1);
       mfma(c0, M);
       __builtin_amdgcn_sched_barrier(0);
     });
     // step 1
-    static_for<16>([&](auto M) {
-      if constexpr ((M & 1) == 0) read_frag(c0, std::integral_constant<int, M / 2>{}, stage, 2);
+    static_for<8>([&](auto M) {
+      if constexpr (M < 6) read_frag(c0, M, stage, 2);
       mfma(c1, M);
       __builtin_amdgcn_sched_barrier(0);
     });
     // step 2: also move operand A of the next tile into LDS and refill its registers
-    static_for<16>([&](auto M) {
-      if constexpr ((M & 1) == 0) {
-        read_frag(c1, std::integral_constant<int, M / 2>{}, stage, 3);
-      } else {
+    static_for<8>([&](auto M) {
+      if constexpr (M < 6) read_frag(c1, M, stage, 3);
+      if constexpr ((M & 1) == 1) {
         store_piece<A_TRANS>(next, ra[M / 2], M / 2);
         load_a(q2, M / 2);
       }
@@ -376,7 +378,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
       __builtin_amdgcn_sched_barrier(0);
     });
     // step 3, first half: operand B likewise
-    static_for<8>([&](auto M) {
+    static_for<4>([&](auto M) {
       store_piece<B_TRANS>(next + kTileBytes, rb[M], M);
       load_b(q2, M);
       mfma(c1, M);
@@ -385,16 +387,19 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
     // step 3, second half, with the next tile's first fragments in flight
-    static_for<8>([&](auto M) {
-      read_frag(c0, M, stage ^ 1, 0);
-      mfma(c1, std::integral_constant<int, M + 8>{});
+    static_for<4>([&](auto M) {
+      if constexpr (M < 3) {
+        read_frag(c0, std::integral_constant<int, 2 * M>{}, stage ^ 1, 0);
+        read_frag(c0, std::integral_constant<int, 2 * M + 1>{}, stage ^ 1, 0);
+      }
+      mfma(c1, std::integral_constant<int, M + 4>{});
       __builtin_amdgcn_sched_barrier(0);
     });
   }
   __syncthreads();
 
   // ---- epilogue.  Accumulator element r of block (i, j) is row i*32 + (r/4)*8 +
-  // (lane/32)*4 + r%4, column j*32 + lane%32 of the wavefront's 128x128 part.  Each
+  // (lane/32)*4 + r%4, column j*32 + lane%32 of the wavefront's 64x128 part.  Each
   // wavefront passes one 32-row band at a time through its own LDS patch (fp32,
   // padded rows) so that global memory sees 16-byte accesses along rows.
   float* ep = (float*)(smem + wave * kEpWaveBytes);
@@ -404,7 +409,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   bf16_t* __restrict__ C1 = p.C1;
   bf16_t* __restrict__ C2 = p.C2;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < 2; ++i) {
     if (i > 0) __syncthreads();
 #pragma unroll
     for (int j = 0; j < 4; ++j)
@@ -412,7 +417,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
       for (int r = 0; r < 16; ++r)
         ep[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * kEpPitch + j * 32 + (lane & 31)] = acc[i][j][r];
     __syncthreads();
-    const int band_row = t.m0 + wm * 128 + i * 32;
+    const int band_row = t.m0 + wm * 64 + i * 32;
     if (MODE == MODE_GATEUP) {
       // LDS row: 64 gate columns then the 64 matching up columns
 #pragma unroll
