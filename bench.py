@@ -27,6 +27,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default 2: Mixtral-shaped MoE)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed region, run one plain 1 GiB device copy (a known-size reference for "
+                         "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="tokens in the oracle's timed sample (0 = auto)")
     return ap.parse_args()
 
@@ -180,6 +183,14 @@ def main():
         pb = B.dynmo_stage_loads(per_task, pb_bounds)
         imb = {"stages": S, "tasks": "layers" if L > 1 else "experts", "uniform": round(B.dynmo_imbalance(ub), 4),
                "partition": round(B.dynmo_imbalance(pb), 4)}
+
+    if a.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)  # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     cpu = None
     if not a.no_cpu_baseline:

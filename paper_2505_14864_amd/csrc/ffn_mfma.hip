@@ -19,10 +19,10 @@
 // HBM or by scalar LDS traffic.
 //
 // Ragged rows: the row-tile list is derived on the device from seg_offsets, so
-// no host synchronisation is needed; the grid is sized for the worst case and
-// surplus workgroups exit.  Workgroup ids are remapped so that each XCD (ids
-// congruent modulo 8) works on one contiguous run of tiles, ordered so that
-// neighbours share operand tiles in that XCD's L2.
+// no host synchronisation is needed.  One persistent workgroup per compute unit
+// walks the tile list; each XCD (workgroup ids congruent modulo 8) works on one
+// contiguous run of tiles, ordered so that neighbours share operand tiles in that
+// XCD's L2.
 #include <type_traits>
 #include <utility>
 
@@ -44,6 +44,7 @@ constexpr int kPitchK = 144;                 // bytes per row of a [row][k] tile
 constexpr int kPitchT = 576;                 // bytes per k-row of a [k][row] tile: 256 bf16 + 64 pad
 constexpr int kTileBytes = 256 * kPitchK;    // == 64 * kPitchT == 36864
 constexpr int kLdsBytes = 4 * kTileBytes;    // two stages of (A, B)
+constexpr int kTableBytes = 64 * 4 * 4;      // the per-expert tile table, kept behind the stages
 constexpr int kEpPitch = 136;                // floats per row of an epilogue LDS patch (128 + 8 pad)
 constexpr int kEpWaveBytes = 32 * kEpPitch * 4;  // one 32-row band per wavefront
 constexpr int kXcds = 8;
@@ -173,56 +174,70 @@ struct Tile {
   int m0;      // first output row (absolute row for the segmented modes)
   int m_end;   // end of valid rows
   int n0;      // first output column
+  int k_begin, k_end;  // the expert's row range (the contraction range of MODE_DW)
 };
 
-// Segmented modes.  Tiles of one expert form a block; inside it column tiles go in
-// groups of kGroupN and row tiles vary fastest inside a group... see file header.
-__device__ __forceinline__ bool schedule_segmented(const int32_t* __restrict__ seg, int E, int n_tiles, int bn, Tile* t) {
-  int total = 0;
-  for (int e = 0; e < E; ++e) total += ((seg[e + 1] - seg[e] + BM - 1) / BM) * n_tiles;
-  const int per_xcd = (total + kXcds - 1) / kXcds;
-  const int xcd = blockIdx.x % kXcds, i = blockIdx.x / kXcds;
-  const int logical = xcd * per_xcd + i;
-  if (i >= per_xcd || logical >= total) return false;
-  int first = 0;
-  for (int e = 0; e < E; ++e) {
-    const int begin = seg[e], end = seg[e + 1];
-    const int mt = (end - begin + BM - 1) / BM;
-    const int tiles = mt * n_tiles;
-    if (logical < first + tiles) {
-      const int r = logical - first;
-      const int group = r / (mt * kGroupN);
-      const int within = r - group * (mt * kGroupN);
-      const int gn = min(kGroupN, n_tiles - group * kGroupN);
-      const int mi = within / gn, ni = group * kGroupN + within % gn;
-      t->e = e;
-      t->m0 = begin + mi * BM;
-      t->m_end = end;
-      t->n0 = ni * bn;
-      return true;
-    }
-    first += tiles;
+// The tile list is never materialised.  Lane e of every wavefront keeps expert
+// e's row range and the running count of tiles up to and including that expert;
+// a flat tile index is turned into (expert, row tile, column tile) with one ballot
+// and a few lane reads.  Tiles of one expert form a block; inside it the column
+// tiles go in groups of kGroupN and, inside a group, consecutive indices walk the
+// column tiles of one row tile before moving to the next row tile, so that the 32
+// workgroups of an XCD hold a 4 x 8 patch of tiles that share operand tiles in L2.
+struct TileTable {
+  int nt;     // column tiles (same for all experts)
+  int total;  // tiles of all experts
+};
+
+// Per expert e, at table[4*e ..]: first row, end row, row tiles, tiles of experts 0..e.
+// Built by the first wavefront into LDS (kept there so that it costs no registers
+// during the main loop); callers synchronise before reading it.
+__device__ __forceinline__ TileTable make_tile_table(int* table, const int32_t* __restrict__ seg, int E, bool dw, int M,
+                                                     int N, int tile_n) {
+  const int lane = threadIdx.x & 63;
+  TileTable tb;
+  tb.nt = (N + tile_n - 1) / tile_n;
+  int begin = 0, end = 0;
+  if (lane < E) {
+    begin = seg[lane];
+    end = seg[lane + 1];
   }
-  return false;
+  const int mt = dw ? (lane < E ? (M + BM - 1) / BM : 0) : (end - begin + BM - 1) / BM;
+  int v = mt * tb.nt;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int o = __shfl_up(v, d, 64);
+    if (lane >= d) v += o;
+  }
+  tb.total = __builtin_amdgcn_readlane(v, 63);
+  if (threadIdx.x < 64) {
+    table[4 * lane + 0] = begin;
+    table[4 * lane + 1] = end;
+    table[4 * lane + 2] = mt;
+    table[4 * lane + 3] = v;
+  }
+  return tb;
 }
 
-// MODE_DW: every expert has the same (M/BM) x (N/BN) grid of output tiles.
-__device__ __forceinline__ bool schedule_dw(int E, int M, int N, Tile* t) {
-  const int mt = (M + BM - 1) / BM, nt = (N + BN - 1) / BN;
-  const int total = E * mt * nt;
-  const int per_xcd = (total + kXcds - 1) / kXcds;
-  const int xcd = blockIdx.x % kXcds, i = blockIdx.x / kXcds;
-  const int logical = xcd * per_xcd + i;
-  if (i >= per_xcd || logical >= total) return false;
-  const int e = logical / (mt * nt), r = logical % (mt * nt);
+__device__ __forceinline__ Tile decode_tile(const int* table, const TileTable& tb, int logical, bool dw, int M, int tile_n) {
+  const int lane = threadIdx.x & 63;
+  const unsigned long long mask = __ballot(table[4 * lane + 3] > logical);
+  const int e = __builtin_ctzll(mask);
+  const int begin = table[4 * e + 0], end = table[4 * e + 1], mt = table[4 * e + 2];
+  const int first = table[4 * e + 3] - mt * tb.nt;
+  const int r = logical - first;
   const int group = r / (mt * kGroupN);
   const int within = r - group * (mt * kGroupN);
-  const int gn = min(kGroupN, nt - group * kGroupN);
-  t->e = e;
-  t->m0 = (within / gn) * BM;
-  t->m_end = M;
-  t->n0 = (group * kGroupN + within % gn) * BN;
-  return true;
+  const int gn = min(kGroupN, tb.nt - group * kGroupN);
+  const int mi = within / gn, ni = group * kGroupN + within % gn;
+  Tile t;
+  t.e = e;
+  t.m0 = dw ? mi * BM : begin + mi * BM;
+  t.m_end = dw ? M : end;
+  t.n0 = ni * tile_n;
+  t.k_begin = begin;  // MODE_DW contracts over the expert's rows
+  t.k_end = end;
+  return t;
 }
 
 template <int... Is, typename F>
@@ -244,25 +259,28 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   constexpr bool B_TRANS = MODE == MODE_DA || MODE == MODE_DX || MODE == MODE_DW;
   constexpr int TILE_N = MODE == MODE_GATEUP ? 128 : BN;  // output columns per tile
 
-  Tile t;
-  if (MODE == MODE_DW) {
-    if (!schedule_dw(p.E, p.M, p.N, &t)) return;
-  } else {
-    if (!schedule_segmented(p.seg, p.E, (p.N + TILE_N - 1) / TILE_N, TILE_N, &t)) return;
-  }
+  // Persistent workgroups: workgroup b belongs to XCD b % 8 (the hardware deals
+  // workgroup ids round-robin over the XCDs) and is the (b / 8)-th of its XCD.  Each
+  // XCD owns one contiguous run of the tile list, which its workgroups walk in
+  // lock step, so neighbouring tiles run at the same time in one L2.
+  int* table = (int*)(smem + kLdsBytes);
+  const TileTable tb = make_tile_table(table, p.seg, p.E, MODE == MODE_DW, p.M, p.N, TILE_N);
+  __syncthreads();
+  const int per_xcd = (tb.total + kXcds - 1) / kXcds;
+  const int xcd = blockIdx.x % kXcds, slots = gridDim.x / kXcds;
+  const int n_end = p.N;
+  for (int it = blockIdx.x / kXcds; it < per_xcd; it += slots) {
+  const int logical = xcd * per_xcd + it;
+  if (logical >= tb.total) break;
+  const Tile t = decode_tile(table, tb, logical, MODE == MODE_DW, p.M, TILE_N);
 
   // contraction range and per-expert operand bases
-  int k_begin = 0, k_end = p.K;
-  if (MODE == MODE_DW) {
-    k_begin = p.seg[t.e];
-    k_end = p.seg[t.e + 1];
-  }
+  const int k_begin = MODE == MODE_DW ? t.k_begin : 0, k_end = MODE == MODE_DW ? t.k_end : p.K;
   const bf16_t* B1 = p.B1 + (MODE == MODE_DW ? 0 : (long)t.e * p.b_expert_stride);
   const bf16_t* B2 = (MODE == MODE_GATEUP || MODE == MODE_DX) ? p.B2 + (long)t.e * p.b_expert_stride : nullptr;
   const int phases = MODE == MODE_DX ? 2 : 1;
   const int kt_per_phase = (k_end - k_begin + BK - 1) / BK;
   const int n_kt = kt_per_phase * phases;
-  const int n_end = p.N;
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm = wave >> 1, wn = wave & 1;  // 4 x 2 wavefronts, 64 x 128 outputs each
@@ -465,19 +483,37 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
       }
     }
   }
+  __syncthreads();  // the LDS patches are reused by the next tile's staging
+  }  // tile loop
+}
+
+// Workgroups are persistent: one per compute unit (the LDS and register use allow
+// no more), capped by the number of tiles the shapes can produce.
+static int persistent_blocks(int max_tiles) {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        n <= 0)
+      n = 256;
+    cus = n / kXcds * kXcds;
+    if (cus < kXcds) cus = kXcds;
+  }
+  const int want = (max_tiles + kXcds - 1) / kXcds * kXcds;
+  return want < cus ? want : cus;
 }
 
 template <int MODE>
-static int32_t launch_mfma(const GemmParams& p, int blocks, KernelId id, hipStream_t st) {
+static int32_t launch_mfma(const GemmParams& p, int max_tiles, KernelId id, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
     DYNMO_HIP_TRY(hipFuncSetAttribute((const void*)ffn_mfma_kernel<MODE>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      kLdsBytes));
+                                      kLdsBytes + kTableBytes));
     attr_set = true;
   }
-  if (blocks <= 0) return DYNMO_OK;
-  blocks = (blocks + kXcds - 1) / kXcds * kXcds;
-  DYNMO_TIMED_LAUNCH(id, st, ffn_mfma_kernel<MODE><<<dim3(blocks), dim3(kMfmaThreads), kLdsBytes, st>>>(p));
+  if (max_tiles <= 0) return DYNMO_OK;
+  const int blocks = persistent_blocks(max_tiles);
+  DYNMO_TIMED_LAUNCH(id, st, ffn_mfma_kernel<MODE><<<dim3(blocks), dim3(kMfmaThreads), kLdsBytes + kTableBytes, st>>>(p));
   return DYNMO_OK;
 }
 
