@@ -6,7 +6,12 @@
 
 namespace dynmo {
 
-template <typename T>
+// Both kernels give one wavefront to a token and walk its row in groups of
+// kUnroll x 64 sixteen-byte pieces: all loads of a group are issued before any of
+// them is used, so each lane keeps (slots + 1) x kUnroll loads in flight.
+constexpr int kUnroll = 4;
+
+template <typename T, int MAXK>
 __global__ __launch_bounds__(256) void combine_kernel(const u32x4* __restrict__ y_p, const int32_t* __restrict__ dst_pos,
                                                       const float* __restrict__ gate_w, const u32x4* __restrict__ base,
                                                       u32x4* __restrict__ out, int Tn, int k, int row_vecs) {
@@ -14,11 +19,11 @@ __global__ __launch_bounds__(256) void combine_kernel(const u32x4* __restrict__ 
   const int lane = threadIdx.x & 63;
   const long t = ((long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
   if (t >= Tn) return;
-  long src[kMaxCombineSlots];
-  float w[kMaxCombineSlots];
+  long src[MAXK];
+  float w[MAXK];
   bool any = false;
 #pragma unroll
-  for (int s = 0; s < kMaxCombineSlots; ++s) {
+  for (int s = 0; s < MAXK; ++s) {
     src[s] = -1;
     w[s] = 0.f;
     if (s < k) {
@@ -30,36 +35,54 @@ __global__ __launch_bounds__(256) void combine_kernel(const u32x4* __restrict__ 
       }
     }
   }
+  const u32x4* brow = base ? base + t * row_vecs : nullptr;
+  u32x4* orow = out + t * row_vecs;
   if (!any) {  // unrouted token: pass the base through (or zeros)
     for (int c = lane; c < row_vecs; c += 64) {
       u32x4 v = {0, 0, 0, 0};
-      if (base) v = base[t * row_vecs + c];
-      out[t * row_vecs + c] = v;
+      if (brow) v = brow[c];
+      orow[c] = v;
     }
     return;
   }
-  for (int c = lane; c < row_vecs; c += 64) {
-    float acc[V];
-    if (base) {
-      unpack16<T>(base[t * row_vecs + c], acc);
-    } else {
+  for (int c0 = lane; c0 < row_vecs; c0 += 64 * kUnroll) {
+    u32x4 yv[MAXK][kUnroll], bv[kUnroll];
 #pragma unroll
-      for (int j = 0; j < V; ++j) acc[j] = 0.f;
+    for (int u = 0; u < kUnroll; ++u) {
+      bv[u] = u32x4{0, 0, 0, 0};
+      if (brow && c0 + 64 * u < row_vecs) bv[u] = brow[c0 + 64 * u];
     }
 #pragma unroll
-    for (int s = 0; s < kMaxCombineSlots; ++s) {
+    for (int s = 0; s < MAXK; ++s)
       if (src[s] >= 0) {
-        float f[V];
-        unpack16<T>(y_p[src[s] + c], f);
 #pragma unroll
-        for (int j = 0; j < V; ++j) acc[j] += w[s] * f[j];
+        for (int u = 0; u < kUnroll; ++u)
+          if (c0 + 64 * u < row_vecs) yv[s][u] = y_p[src[s] + c0 + 64 * u];
       }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      if (c0 + 64 * u >= row_vecs) continue;
+      float acc[V];
+      if (brow) {
+        unpack16<T>(bv[u], acc);
+      } else {
+#pragma unroll
+        for (int j = 0; j < V; ++j) acc[j] = 0.f;
+      }
+#pragma unroll
+      for (int s = 0; s < MAXK; ++s)
+        if (src[s] >= 0) {
+          float f[V];
+          unpack16<T>(yv[s][u], f);
+#pragma unroll
+          for (int j = 0; j < V; ++j) acc[j] += w[s] * f[j];
+        }
+      orow[c0 + 64 * u] = pack16<T>(acc);
     }
-    out[t * row_vecs + c] = pack16<T>(acc);
   }
 }
 
-template <typename T>
+template <typename T, int MAXK>
 __global__ __launch_bounds__(256) void combine_bwd_kernel(const u32x4* __restrict__ dout, const u32x4* __restrict__ y_p,
                                                           const int32_t* __restrict__ dst_pos,
                                                           const float* __restrict__ gate_w, u32x4* __restrict__ dy_p,
@@ -68,12 +91,12 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const u32x4* __restric
   const int lane = threadIdx.x & 63;
   const long t = ((long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
   if (t >= Tn) return;
-  long row[kMaxCombineSlots];
-  float w[kMaxCombineSlots];
-  float dot[kMaxCombineSlots];
+  long row[MAXK];
+  float w[MAXK];
+  float dot[MAXK];
   bool any = false;
 #pragma unroll
-  for (int s = 0; s < kMaxCombineSlots; ++s) {
+  for (int s = 0; s < MAXK; ++s) {
     row[s] = -1;
     w[s] = 0.f;
     dot[s] = 0.f;
@@ -87,26 +110,41 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const u32x4* __restric
     }
   }
   if (any) {
-    for (int c = lane; c < row_vecs; c += 64) {
-      float d[V];
-      unpack16<T>(dout[t * row_vecs + c], d);
+    const u32x4* drow = dout + t * row_vecs;
+    for (int c0 = lane; c0 < row_vecs; c0 += 64 * kUnroll) {
+      u32x4 dv[kUnroll], yv[MAXK][kUnroll];
 #pragma unroll
-      for (int s = 0; s < kMaxCombineSlots; ++s) {
+      for (int u = 0; u < kUnroll; ++u)
+        if (c0 + 64 * u < row_vecs) dv[u] = drow[c0 + 64 * u];
+#pragma unroll
+      for (int s = 0; s < MAXK; ++s)
         if (row[s] >= 0) {
-          float y[V], o[V];
-          unpack16<T>(y_p[row[s] + c], y);
 #pragma unroll
-          for (int j = 0; j < V; ++j) {
-            dot[s] += d[j] * y[j];
-            o[j] = w[s] * d[j];
-          }
-          dy_p[row[s] + c] = pack16<T>(o);
+          for (int u = 0; u < kUnroll; ++u)
+            if (c0 + 64 * u < row_vecs) yv[s][u] = y_p[row[s] + c0 + 64 * u];
         }
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        if (c0 + 64 * u >= row_vecs) continue;
+        float d[V];
+        unpack16<T>(dv[u], d);
+#pragma unroll
+        for (int s = 0; s < MAXK; ++s)
+          if (row[s] >= 0) {
+            float y[V], o[V];
+            unpack16<T>(yv[s][u], y);
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+              dot[s] += d[j] * y[j];
+              o[j] = w[s] * d[j];
+            }
+            dy_p[row[s] + c0 + 64 * u] = pack16<T>(o);
+          }
       }
     }
   }
 #pragma unroll
-  for (int s = 0; s < kMaxCombineSlots; ++s) {
+  for (int s = 0; s < MAXK; ++s) {
     if (s < k) {
       float v = dot[s];
 #pragma unroll
@@ -121,10 +159,20 @@ static int32_t launch_combine(const dynmo_desc* d, const void* y_p, const int32_
                               const void* base, void* out, hipStream_t st) {
   const int row_vecs = (int)((size_t)d->H * sizeof(T) / 16);
   const unsigned blocks = (unsigned)(((int64_t)d->T * 64 + 255) / 256);
-  DYNMO_TIMED_LAUNCH(K_COMBINE, st,
-                     combine_kernel<T><<<dim3(blocks), dim3(256), 0, st>>>((const u32x4*)y_p, dst_pos, gate_w,
-                                                                           (const u32x4*)base, (u32x4*)out, d->T, d->k,
-                                                                           row_vecs));
+#define DYNMO_COMBINE_LAUNCH(MAXK)                                                                              \
+  DYNMO_TIMED_LAUNCH(K_COMBINE, st,                                                                             \
+                     combine_kernel<T, MAXK><<<dim3(blocks), dim3(256), 0, st>>>(                               \
+                         (const u32x4*)y_p, dst_pos, gate_w, (const u32x4*)base, (u32x4*)out, d->T, d->k, row_vecs))
+  if (d->k == 1) {
+    DYNMO_COMBINE_LAUNCH(1);
+  } else if (d->k == 2) {
+    DYNMO_COMBINE_LAUNCH(2);
+  } else if (d->k <= 4) {
+    DYNMO_COMBINE_LAUNCH(4);
+  } else {
+    DYNMO_COMBINE_LAUNCH(kMaxCombineSlots);
+  }
+#undef DYNMO_COMBINE_LAUNCH
   return DYNMO_OK;
 }
 
@@ -133,10 +181,20 @@ static int32_t launch_combine_bwd(const dynmo_desc* d, const void* dout, const v
                                   const float* gate_w, void* dy_p, float* dgate, hipStream_t st) {
   const int row_vecs = (int)((size_t)d->H * sizeof(T) / 16);
   const unsigned blocks = (unsigned)(((int64_t)d->T * 64 + 255) / 256);
-  DYNMO_TIMED_LAUNCH(K_COMBINE_BWD, st,
-                     combine_bwd_kernel<T><<<dim3(blocks), dim3(256), 0, st>>>((const u32x4*)dout, (const u32x4*)y_p,
-                                                                               dst_pos, gate_w, (u32x4*)dy_p, dgate, d->T,
-                                                                               d->k, row_vecs));
+#define DYNMO_COMBINE_BWD_LAUNCH(MAXK)                                                                          \
+  DYNMO_TIMED_LAUNCH(K_COMBINE_BWD, st,                                                                         \
+                     combine_bwd_kernel<T, MAXK><<<dim3(blocks), dim3(256), 0, st>>>(                           \
+                         (const u32x4*)dout, (const u32x4*)y_p, dst_pos, gate_w, (u32x4*)dy_p, dgate, d->T, d->k, row_vecs))
+  if (d->k == 1) {
+    DYNMO_COMBINE_BWD_LAUNCH(1);
+  } else if (d->k == 2) {
+    DYNMO_COMBINE_BWD_LAUNCH(2);
+  } else if (d->k <= 4) {
+    DYNMO_COMBINE_BWD_LAUNCH(4);
+  } else {
+    DYNMO_COMBINE_BWD_LAUNCH(kMaxCombineSlots);
+  }
+#undef DYNMO_COMBINE_BWD_LAUNCH
   return DYNMO_OK;
 }
 

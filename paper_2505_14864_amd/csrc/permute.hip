@@ -149,33 +149,63 @@ __global__ __launch_bounds__(256) void permute_rows_kernel(const u32x4* __restri
   }
 }
 
-// dx[t] = dbase[t] + sum_s dx_p[dst_pos[t,s]]  (fp32 sum in ascending s)
-template <typename T>
+// dx[t] = dbase[t] + sum_s dx_p[dst_pos[t,s]]  (fp32 sum in ascending s).  One wavefront
+// per token; the row is walked in groups of 4 x 64 pieces with all loads of a group
+// issued before any is used.
+template <typename T, int MAXK>
 __global__ __launch_bounds__(256) void permute_bwd_kernel(const u32x4* __restrict__ dx_p, const int32_t* __restrict__ dst_pos,
                                                           const u32x4* __restrict__ dbase, u32x4* __restrict__ dx, int Tn,
                                                           int k, int row_vecs) {
   constexpr int V = Elem<T>::kVec;
+  constexpr int U = 4;
   const int lane = threadIdx.x & 63;
   const long t = ((long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
   if (t >= Tn) return;
-  for (int c = lane; c < row_vecs; c += 64) {
-    float acc[V];
-    if (dbase) {
-      unpack16<T>(dbase[t * row_vecs + c], acc);
-    } else {
+  long src[MAXK];
 #pragma unroll
-      for (int j = 0; j < V; ++j) acc[j] = 0.f;
-    }
-    for (int s = 0; s < k; ++s) {
+  for (int s = 0; s < MAXK; ++s) {
+    src[s] = -1;
+    if (s < k) {
       const int p = dst_pos[t * k + s];
-      if (p >= 0) {
-        float f[V];
-        unpack16<T>(dx_p[(long)p * row_vecs + c], f);
-#pragma unroll
-        for (int j = 0; j < V; ++j) acc[j] += f[j];
-      }
+      if (p >= 0) src[s] = (long)p * row_vecs;
     }
-    dx[t * row_vecs + c] = pack16<T>(acc);
+  }
+  const u32x4* brow = dbase ? dbase + t * row_vecs : nullptr;
+  u32x4* orow = dx + t * row_vecs;
+  for (int c0 = lane; c0 < row_vecs; c0 += 64 * U) {
+    u32x4 bv[U], xv[MAXK][U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      bv[u] = u32x4{0, 0, 0, 0};
+      if (brow && c0 + 64 * u < row_vecs) bv[u] = brow[c0 + 64 * u];
+    }
+#pragma unroll
+    for (int s = 0; s < MAXK; ++s)
+      if (src[s] >= 0) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (c0 + 64 * u < row_vecs) xv[s][u] = dx_p[src[s] + c0 + 64 * u];
+      }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (c0 + 64 * u >= row_vecs) continue;
+      float acc[V];
+      if (brow) {
+        unpack16<T>(bv[u], acc);
+      } else {
+#pragma unroll
+        for (int j = 0; j < V; ++j) acc[j] = 0.f;
+      }
+#pragma unroll
+      for (int s = 0; s < MAXK; ++s)
+        if (src[s] >= 0) {
+          float f[V];
+          unpack16<T>(xv[s][u], f);
+#pragma unroll
+          for (int j = 0; j < V; ++j) acc[j] += f[j];
+        }
+      orow[c0 + 64 * u] = pack16<T>(acc);
+    }
   }
 }
 
@@ -196,10 +226,22 @@ static int32_t launch_permute_bwd(const dynmo_desc* d, const void* dx_p, const i
                                   void* dx, hipStream_t st) {
   const int row_vecs = (int)((size_t)d->H * sizeof(T) / 16);
   const unsigned blocks = (unsigned)(((int64_t)d->T * 64 + 255) / 256);
-  DYNMO_TIMED_LAUNCH(K_PERMUTE_BWD, st,
-                     permute_bwd_kernel<T><<<dim3(blocks), dim3(256), 0, st>>>((const u32x4*)dx_p, dst_pos,
-                                                                               (const u32x4*)dbase, (u32x4*)dx, d->T, d->k,
-                                                                               row_vecs));
+#define DYNMO_PERMUTE_BWD_LAUNCH(MAXK)                                                                          \
+  DYNMO_TIMED_LAUNCH(K_PERMUTE_BWD, st,                                                                         \
+                     permute_bwd_kernel<T, MAXK><<<dim3(blocks), dim3(256), 0, st>>>(                           \
+                         (const u32x4*)dx_p, dst_pos, (const u32x4*)dbase, (u32x4*)dx, d->T, d->k, row_vecs))
+  if (d->k == 1) {
+    DYNMO_PERMUTE_BWD_LAUNCH(1);
+  } else if (d->k == 2) {
+    DYNMO_PERMUTE_BWD_LAUNCH(2);
+  } else if (d->k <= 4) {
+    DYNMO_PERMUTE_BWD_LAUNCH(4);
+  } else if (d->k <= 8) {
+    DYNMO_PERMUTE_BWD_LAUNCH(8);
+  } else {
+    DYNMO_PERMUTE_BWD_LAUNCH(kMaxExperts);
+  }
+#undef DYNMO_PERMUTE_BWD_LAUNCH
   return DYNMO_OK;
 }
 
