@@ -20,9 +20,9 @@
 //
 // Ragged rows: the row-tile list is derived on the device from seg_offsets, so
 // no host synchronisation is needed.  One persistent workgroup per compute unit
-// walks the tile list; each XCD (workgroup ids congruent modulo 8) works on one
-// contiguous run of tiles, ordered so that neighbours share operand tiles in that
-// XCD's L2.
+// walks the tile list; each XCD (workgroup ids congruent modulo 8) takes an equal
+// share of every expert's tiles, ordered so that neighbours share operand tiles in
+// that XCD's L2.
 #include <type_traits>
 #include <utility>
 
@@ -177,23 +177,27 @@ struct Tile {
   int k_begin, k_end;  // the expert's row range (the contraction range of MODE_DW)
 };
 
-// The tile list is never materialised.  Lane e of every wavefront keeps expert
-// e's row range and the running count of tiles up to and including that expert;
-// a flat tile index is turned into (expert, row tile, column tile) with one ballot
-// and a few lane reads.  Tiles of one expert form a block; inside it the column
-// tiles go in groups of kGroupN and, inside a group, consecutive indices walk the
-// column tiles of one row tile before moving to the next row tile, so that the 32
+// The tile list is never materialised.  Every XCD takes an equal share (one eighth,
+// a contiguous run) of EACH expert's tiles: the products that contract over an
+// expert's rows cost in proportion to its row count, so handing whole experts to
+// XCDs would leave the XCD with the most loaded expert working long after the rest.
+// An XCD walks its shares expert by expert as one flat list; inside an expert the
+// column tiles go in groups of kGroupN and, inside a group, consecutive indices walk
+// the column tiles of one row tile before moving to the next row tile, so that the 32
 // workgroups of an XCD hold a 4 x 8 patch of tiles that share operand tiles in L2.
 struct TileTable {
   int nt;     // column tiles (same for all experts)
-  int total;  // tiles of all experts
+  int total;  // tiles in this XCD's list
 };
 
-// Per expert e, at table[4*e ..]: first row, end row, row tiles, tiles of experts 0..e.
-// Built by the first wavefront into LDS (kept there so that it costs no registers
-// during the main loop); callers synchronise before reading it.
+// Per expert e, at table[4*e ..]: first row, end row, row tiles, and the number of
+// tiles of experts 0..e in this XCD's list.  Built by the first wavefront into LDS
+// (kept there so that it costs no registers during the main loop); callers
+// synchronise before reading it.
+__device__ __forceinline__ int xcd_share_begin(int n_tiles, int xcd) { return (int)((long)n_tiles * xcd / kXcds); }
+
 __device__ __forceinline__ TileTable make_tile_table(int* table, const int32_t* __restrict__ seg, int E, bool dw, int M,
-                                                     int N, int tile_n) {
+                                                     int N, int tile_n, int xcd) {
   const int lane = threadIdx.x & 63;
   TileTable tb;
   tb.nt = (N + tile_n - 1) / tile_n;
@@ -203,7 +207,8 @@ __device__ __forceinline__ TileTable make_tile_table(int* table, const int32_t* 
     end = seg[lane + 1];
   }
   const int mt = dw ? (lane < E ? (M + BM - 1) / BM : 0) : (end - begin + BM - 1) / BM;
-  int v = mt * tb.nt;
+  const int n = mt * tb.nt;
+  int v = xcd_share_begin(n, xcd + 1) - xcd_share_begin(n, xcd);
 #pragma unroll
   for (int d = 1; d < 64; d <<= 1) {
     const int o = __shfl_up(v, d, 64);
@@ -219,13 +224,16 @@ __device__ __forceinline__ TileTable make_tile_table(int* table, const int32_t* 
   return tb;
 }
 
-__device__ __forceinline__ Tile decode_tile(const int* table, const TileTable& tb, int logical, bool dw, int M, int tile_n) {
+// pos = position in this XCD's list
+__device__ __forceinline__ Tile decode_tile(const int* table, const TileTable& tb, int pos, int xcd, bool dw, int M,
+                                            int tile_n) {
   const int lane = threadIdx.x & 63;
-  const unsigned long long mask = __ballot(table[4 * lane + 3] > logical);
+  const unsigned long long mask = __ballot(table[4 * lane + 3] > pos);
   const int e = __builtin_ctzll(mask);
   const int begin = table[4 * e + 0], end = table[4 * e + 1], mt = table[4 * e + 2];
-  const int first = table[4 * e + 3] - mt * tb.nt;
-  const int r = logical - first;
+  const int n = mt * tb.nt;
+  const int lo = xcd_share_begin(n, xcd), share = xcd_share_begin(n, xcd + 1) - lo;
+  const int r = lo + (pos - (table[4 * e + 3] - share));  // tile index inside expert e
   const int group = r / (mt * kGroupN);
   const int within = r - group * (mt * kGroupN);
   const int gn = min(kGroupN, tb.nt - group * kGroupN);
@@ -260,19 +268,16 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   constexpr int TILE_N = MODE == MODE_GATEUP ? 128 : BN;  // output columns per tile
 
   // Persistent workgroups: workgroup b belongs to XCD b % 8 (the hardware deals
-  // workgroup ids round-robin over the XCDs) and is the (b / 8)-th of its XCD.  Each
-  // XCD owns one contiguous run of the tile list, which its workgroups walk in
-  // lock step, so neighbouring tiles run at the same time in one L2.
+  // workgroup ids round-robin over the XCDs) and is the (b / 8)-th of its XCD.  The
+  // workgroups of an XCD walk that XCD's tile list in lock step, so neighbouring
+  // tiles run at the same time in one L2.
   int* table = (int*)(smem + kLdsBytes);
-  const TileTable tb = make_tile_table(table, p.seg, p.E, MODE == MODE_DW, p.M, p.N, TILE_N);
-  __syncthreads();
-  const int per_xcd = (tb.total + kXcds - 1) / kXcds;
   const int xcd = blockIdx.x % kXcds, slots = gridDim.x / kXcds;
+  const TileTable tb = make_tile_table(table, p.seg, p.E, MODE == MODE_DW, p.M, p.N, TILE_N, xcd);
+  __syncthreads();
   const int n_end = p.N;
-  for (int it = blockIdx.x / kXcds; it < per_xcd; it += slots) {
-  const int logical = xcd * per_xcd + it;
-  if (logical >= tb.total) break;
-  const Tile t = decode_tile(table, tb, logical, MODE == MODE_DW, p.M, TILE_N);
+  for (int it = blockIdx.x / kXcds; it < tb.total; it += slots) {
+  const Tile t = decode_tile(table, tb, it, xcd, MODE == MODE_DW, p.M, TILE_N);
 
   // contraction range and per-expert operand bases
   const int k_begin = MODE == MODE_DW ? t.k_begin : 0, k_end = MODE == MODE_DW ? t.k_end : p.K;
