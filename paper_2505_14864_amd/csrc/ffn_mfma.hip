@@ -20,9 +20,8 @@
 //
 // Ragged rows: the row-tile list is derived on the device from seg_offsets, so
 // no host synchronisation is needed.  One persistent workgroup per compute unit
-// walks the tile list; each XCD (workgroup ids congruent modulo 8) takes an equal
-// share of every expert's tiles, ordered so that neighbours share operand tiles in
-// that XCD's L2.
+// walks the tile list; each XCD (workgroup ids congruent modulo 8) takes a share
+// balanced by cost, ordered so that neighbours share operand tiles in that XCD's L2.
 #include <type_traits>
 #include <utility>
 
@@ -44,7 +43,7 @@ constexpr int kPitchK = 144;                 // bytes per row of a [row][k] tile
 constexpr int kPitchT = 576;                 // bytes per k-row of a [k][row] tile: 256 bf16 + 64 pad
 constexpr int kTileBytes = 256 * kPitchK;    // == 64 * kPitchT == 36864
 constexpr int kLdsBytes = 4 * kTileBytes;    // two stages of (A, B)
-constexpr int kTableBytes = 64 * 4 * 4;      // the per-expert tile table, kept behind the stages
+constexpr int kTableBytes = 64 * 8 * 4;      // the per-expert tile table, kept behind the stages
 constexpr int kEpPitch = 136;                // floats per row of an epilogue LDS patch (128 + 8 pad)
 constexpr int kEpWaveBytes = 32 * kEpPitch * 4;  // one 32-row band per wavefront
 constexpr int kXcds = 8;
@@ -177,25 +176,29 @@ struct Tile {
   int k_begin, k_end;  // the expert's row range (the contraction range of MODE_DW)
 };
 
-// The tile list is never materialised.  Every XCD takes an equal share (one eighth,
-// a contiguous run) of EACH expert's tiles: the products that contract over an
-// expert's rows cost in proportion to its row count, so handing whole experts to
-// XCDs would leave the XCD with the most loaded expert working long after the rest.
-// An XCD walks its shares expert by expert as one flat list; inside an expert the
-// column tiles go in groups of kGroupN and, inside a group, consecutive indices walk
-// the column tiles of one row tile before moving to the next row tile, so that the 32
-// workgroups of an XCD hold a 4 x 8 patch of tiles that share operand tiles in L2.
+// The tile list is never materialised.  All tiles of expert 0 come first, then
+// expert 1, ...; inside an expert the column tiles go in groups of kGroupN and,
+// inside a group, consecutive indices walk the column tiles of one row tile before
+// moving to the next row tile, so that the 32 workgroups of an XCD hold a 4 x 8 patch
+// of tiles that share operand tiles in L2.  How the list is dealt to the XCDs
+// depends on what a tile costs:
+//   * row-segmented products: every tile has the same k range, so each XCD takes one
+//     contiguous eighth of the whole list (fewest distinct weight tiles per L2);
+//   * products that contract over an expert's rows: a tile costs in proportion to
+//     the expert's row count, so each XCD takes an eighth of EVERY expert's tiles
+//     (whole experts per XCD would leave the most loaded one working alone).
+// Either way an XCD's share of an expert is one contiguous run, and the XCD walks
+// its runs expert by expert as one flat list.
 struct TileTable {
   int nt;     // column tiles (same for all experts)
   int total;  // tiles in this XCD's list
 };
 
-// Per expert e, at table[4*e ..]: first row, end row, row tiles, and the number of
-// tiles of experts 0..e in this XCD's list.  Built by the first wavefront into LDS
-// (kept there so that it costs no registers during the main loop); callers
-// synchronise before reading it.
-__device__ __forceinline__ int xcd_share_begin(int n_tiles, int xcd) { return (int)((long)n_tiles * xcd / kXcds); }
-
+constexpr int kTableStride = 8;  // ints per expert in the LDS table
+// Per expert e, at table[kTableStride*e ..]: first row, end row, row tiles, number of
+// tiles of experts 0..e in this XCD's list, first tile of this XCD's run inside the
+// expert.  Built by the first wavefront into LDS (kept there so that it costs no
+// registers during the main loop); callers synchronise before reading it.
 __device__ __forceinline__ TileTable make_tile_table(int* table, const int32_t* __restrict__ seg, int E, bool dw, int M,
                                                      int N, int tile_n, int xcd) {
   const int lane = threadIdx.x & 63;
@@ -208,32 +211,47 @@ __device__ __forceinline__ TileTable make_tile_table(int* table, const int32_t* 
   }
   const int mt = dw ? (lane < E ? (M + BM - 1) / BM : 0) : (end - begin + BM - 1) / BM;
   const int n = mt * tb.nt;
-  int v = xcd_share_begin(n, xcd + 1) - xcd_share_begin(n, xcd);
+  auto scan = [&](int v) {
 #pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const int o = __shfl_up(v, d, 64);
-    if (lane >= d) v += o;
+    for (int d = 1; d < 64; d <<= 1) {
+      const int o = __shfl_up(v, d, 64);
+      if (lane >= d) v += o;
+    }
+    return v;
+  };
+  int run_off, run_len;
+  if (dw) {
+    run_off = (int)((long)n * xcd / kXcds);
+    run_len = (int)((long)n * (xcd + 1) / kXcds) - run_off;
+  } else {
+    const int incl = scan(n);
+    const int all = __builtin_amdgcn_readlane(incl, 63);
+    const int per = (all + kXcds - 1) / kXcds;
+    const int lo = max(xcd * per, incl - n), hi = min(min((xcd + 1) * per, all), incl);
+    run_off = lo - (incl - n);
+    run_len = max(hi - lo, 0);
   }
-  tb.total = __builtin_amdgcn_readlane(v, 63);
+  const int cum = scan(run_len);
+  tb.total = __builtin_amdgcn_readlane(cum, 63);
   if (threadIdx.x < 64) {
-    table[4 * lane + 0] = begin;
-    table[4 * lane + 1] = end;
-    table[4 * lane + 2] = mt;
-    table[4 * lane + 3] = v;
+    int* row = table + kTableStride * lane;
+    row[0] = begin;
+    row[1] = end;
+    row[2] = mt;
+    row[3] = cum;
+    row[4] = run_off - (cum - run_len);  // add a list position to get the tile index inside the expert
   }
   return tb;
 }
 
 // pos = position in this XCD's list
-__device__ __forceinline__ Tile decode_tile(const int* table, const TileTable& tb, int pos, int xcd, bool dw, int M,
-                                            int tile_n) {
+__device__ __forceinline__ Tile decode_tile(const int* table, const TileTable& tb, int pos, bool dw, int M, int tile_n) {
   const int lane = threadIdx.x & 63;
-  const unsigned long long mask = __ballot(table[4 * lane + 3] > pos);
+  const unsigned long long mask = __ballot(table[kTableStride * lane + 3] > pos);
   const int e = __builtin_ctzll(mask);
-  const int begin = table[4 * e + 0], end = table[4 * e + 1], mt = table[4 * e + 2];
-  const int n = mt * tb.nt;
-  const int lo = xcd_share_begin(n, xcd), share = xcd_share_begin(n, xcd + 1) - lo;
-  const int r = lo + (pos - (table[4 * e + 3] - share));  // tile index inside expert e
+  const int* row = table + kTableStride * e;
+  const int begin = row[0], end = row[1], mt = row[2];
+  const int r = pos + row[4];  // tile index inside expert e
   const int group = r / (mt * kGroupN);
   const int within = r - group * (mt * kGroupN);
   const int gn = min(kGroupN, tb.nt - group * kGroupN);
@@ -281,7 +299,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   // out (measured: a few percent).
   if (threadIdx.x >= kMfmaThreads / 2) __builtin_amdgcn_s_setprio(1);
   for (int it = blockIdx.x / kXcds; it < tb.total; it += slots) {
-  const Tile t = decode_tile(table, tb, it, xcd, MODE == MODE_DW, p.M, TILE_N);
+  const Tile t = decode_tile(table, tb, it, MODE == MODE_DW, p.M, TILE_N);
 
   // contraction range and per-expert operand bases
   const int k_begin = MODE == MODE_DW ? t.k_begin : 0, k_end = MODE == MODE_DW ? t.k_end : p.K;
