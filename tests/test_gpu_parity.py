@@ -369,3 +369,80 @@ def test_early_exit_full_size():
     loads = [layers[l].load()[1] for l in range(w.layers)]
     assert all(loads[i] >= loads[i + 1] for i in range(w.layers - 1))
     say("  active rows per layer: %s" % [layers[l].load()[0][0] for l in range(w.layers)])
+
+
+# --------------------------------------------------------------------------
+# limits of the boundary, the profiling step, and a few more edge shapes
+# --------------------------------------------------------------------------
+
+def test_many_experts_and_slots():
+    """E = 64 (the limit) with k = 8 (the combine limit), bf16, ragged sizes."""
+    say("moe E=64 k=8")
+    w = wl.scaled(wl.CONFIGS[3], T=300, H=64, F=72, E=64, k=8, seed=51)
+    inp = wl.make_inputs(w, threads=1)
+    layer = run_moe(w, inp)
+    f = f32_inputs(inp)
+    ref = orc.moe_layer(f["logits"], f["x"], f["Wg"], f["Wu"], f["Wd"], w.k, f["dout"])
+    assert np.array_equal(to_host(layer.expert_idx), ref["expert_idx"])
+    check_layer_full(layer, ref, w.dtype)
+    assert_close("dlogits", to_host(layer.droute), ref["dlogits"], TOL[w.dtype])
+
+
+def test_one_expert_takes_more_than_half():
+    """An adversarial histogram: one expert gets most rows, one gets none."""
+    say("moe adversarial histogram")
+    w = wl.scaled(wl.CONFIGS[2], T=1500, H=128, F=256, E=8, k=2, seed=52)
+    inp = wl.make_inputs(w, threads=1)
+    inp["logits"][:, 3] += 6.0   # everybody's first choice
+    inp["logits"][:, 5] -= 40.0  # nobody's choice
+    layer = run_moe(w, inp)
+    f = f32_inputs(inp)
+    ref = orc.moe_layer(f["logits"], f["x"], f["Wg"], f["Wu"], f["Wd"], w.k, f["dout"])
+    counts, _ = layer.load()
+    assert counts[3] == w.T and counts[5] == 0
+    check_layer_full(layer, ref, w.dtype)
+
+
+def test_profiling_step_reports_every_kernel():
+    """The per-kernel event timing of the profiling step: counts match the launches
+    made while it was on, durations are positive, and it is off by default."""
+    say("profiling step")
+    w = wl.scaled(wl.CONFIGS[2], T=512, H=256, F=512, seed=53)
+    inp = wl.make_inputs(w, threads=1)
+    B.dynmo_profile_enable(False)
+    B.dynmo_profile_reset()
+    run_moe(w, inp)
+    assert all(B.dynmo_profile_read(i)[1] == 0 for i in range(B.dynmo_profile_kernel_count()))
+    B.dynmo_profile_enable(True)
+    run_moe(w, inp)
+    run_moe(w, inp)
+    B.dynmo_profile_enable(False)
+    got = {B.dynmo_profile_kernel_name(i): B.dynmo_profile_read(i) for i in range(B.dynmo_profile_kernel_count())}
+    for name in ("route_topk", "permute_count", "permute_scan", "permute_scatter", "permute_rows", "ffn_gateup", "ffn_down",
+                 "combine", "combine_bwd", "ffn_dA", "ffn_dX", "ffn_dWd", "ffn_dWg", "ffn_dWu", "permute_bwd",
+                 "route_topk_bwd"):
+        ms, n = got[name]
+        assert n == 2 and ms > 0.0, name
+    assert got["route_capacity"][1] == 0
+    by_time = sum(ms for ms, n in got.values()) / 2  # the layer's "by Time" load (Sec. 5)
+    assert 0.0 < by_time < 1000.0
+    B.dynmo_profile_reset()
+
+
+def test_bad_arguments_on_the_gpu():
+    d = B.make_desc(64, 64, 64, 4, 2, "bf16")
+    x = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
+    ei = torch.zeros((64, 2), dtype=torch.int32, device="cuda")
+    small_ws = torch.empty((1,), dtype=torch.uint8, device="cuda")
+    big = torch.empty((128, 64), dtype=torch.bfloat16, device="cuda")
+    seg = torch.empty((5,), dtype=torch.int32, device="cuda")
+    with pytest.raises(B.DynmoError) as e:
+        B.dynmo_grouped_ffn_fwd(d, big, seg, big, big, big, big, big, big, small_ws)
+    assert e.value.status == -3  # DYNMO_EWORKSPACE
+    with pytest.raises(B.DynmoError) as e:
+        B.dynmo_combine(d, big, ei, torch.zeros((64, 2), device="cuda"), x, x)
+    assert e.value.status == -1  # out aliases base
+    d9 = B.make_desc(64, 64, 64, 16, 9, "bf16")
+    with pytest.raises(B.DynmoError) as e:
+        B.dynmo_combine(d9, big, ei, torch.zeros((64, 2), device="cuda"), None, x)
+    assert e.value.status == -2  # more than 8 slots
