@@ -10,6 +10,7 @@ thread_local int32_t g_last_hip_error = 0;
 static size_t act_bytes(const dynmo_desc* d) {  // one [T*k, F] activation buffer
   return align_up((size_t)d->T * d->k * d->F * elem_bytes(d->dtype), 256);
 }
+static size_t mfma_scratch(const dynmo_desc* d) { return ffn_mfma_supported(d) ? ffn_mfma_scratch_bytes() : 0; }
 }  // namespace dynmo
 
 extern "C" int32_t dynmo_version(void) { return 1; }
@@ -17,12 +18,12 @@ extern "C" int32_t dynmo_last_hip_error(void) { return g_last_hip_error; }
 
 extern "C" size_t dynmo_grouped_ffn_fwd_workspace_bytes(const dynmo_desc* d) {
   if (check_desc(d)) return 0;
-  return act_bytes(d) + 256;  // A = silu(G) U
+  return act_bytes(d) + mfma_scratch(d) + 256;  // A = silu(G) U
 }
 
 extern "C" size_t dynmo_grouped_ffn_bwd_workspace_bytes(const dynmo_desc* d) {
   if (check_desc(d)) return 0;
-  return 3 * act_bytes(d) + 256;  // dG, dU, A
+  return 3 * act_bytes(d) + mfma_scratch(d) + 256;  // dG, dU, A
 }
 
 extern "C" int32_t dynmo_grouped_ffn_fwd(const dynmo_desc* d, const void* x_p, const int32_t* seg_offsets,
@@ -35,7 +36,8 @@ extern "C" int32_t dynmo_grouped_ffn_fwd(const dynmo_desc* d, const void* x_p, c
   if (max_m_tiles(d, 64) > 65535) return DYNMO_EUNSUPPORTED;
   void* A = (void*)align_up((size_t)workspace, 256);
   if (ffn_mfma_supported(d))
-    return ffn_fwd_mfma(d, x_p, seg_offsets, Wg, Wu, Wd, y_p, G_save, U_save, A, (hipStream_t)stream);
+    return ffn_fwd_mfma(d, x_p, seg_offsets, Wg, Wu, Wd, y_p, G_save, U_save, A, (char*)A + act_bytes(d),
+                        (hipStream_t)stream);
   return ffn_fwd_generic(d, x_p, seg_offsets, Wg, Wu, Wd, y_p, G_save, U_save, A, (hipStream_t)stream);
 }
 
@@ -56,7 +58,7 @@ extern "C" int32_t dynmo_grouped_ffn_bwd(const dynmo_desc* d, const void* dy_p, 
   void* A = base + 2 * act_bytes(d);
   if (ffn_mfma_supported(d))
     return ffn_bwd_mfma(d, dy_p, x_p, G_save, U_save, seg_offsets, Wg, Wu, Wd, dx_p, dWg, dWu, dWd, dG, dU, A,
-                        (hipStream_t)stream);
+                        base + 3 * act_bytes(d), (hipStream_t)stream);
   return ffn_bwd_generic(d, dy_p, x_p, G_save, U_save, seg_offsets, Wg, Wu, Wd, dx_p, dWg, dWu, dWd, dG, dU, A,
                          (hipStream_t)stream);
 }

@@ -48,6 +48,10 @@ constexpr int kEpPitch = 136;                // floats per row of an epilogue LD
 constexpr int kEpWaveBytes = 32 * kEpPitch * 4;  // one 32-row band per wavefront
 constexpr int kXcds = 8;
 constexpr int kGroupN = 8;                   // column tiles that run side by side in one XCD
+constexpr int kMaxPersistent = 256;          // persistent workgroups per launch (one per compute unit)
+constexpr int kMaxSplit = 8;                 // most k chunks a tile of the last, partly filled round is cut into
+constexpr int kMinSplitKt = 8;               // ... each at least this many k tiles long
+constexpr size_t kPartialBytes = (size_t)BM * BN * 4;  // one workgroup's fp32 partial tile
 
 static_assert(256 * kPitchK == 64 * kPitchT, "both tile layouts must have the same size");
 static_assert((kMfmaThreads / 64) * kEpWaveBytes <= kLdsBytes, "epilogue patches must fit in the staging buffers");
@@ -73,6 +77,8 @@ struct GemmParams {
   long ldc;
   const bf16_t* G;
   const bf16_t* U;
+  float* partial;     // kMaxPersistent partial tiles for the split last round, or nullptr (never split)
+  int32_t* counters;  // kMaxPersistent arrival counters, zero on entry, left zero on exit
 };
 
 // ---- global -> registers -> LDS staging ---------------------------------------
@@ -298,8 +304,25 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   // before the younger one; a higher priority for the younger wavefronts evens that
   // out (measured: a few percent).
   if (threadIdx.x >= kMfmaThreads / 2) __builtin_amdgcn_s_setprio(1);
-  for (int it = blockIdx.x / kXcds; it < tb.total; it += slots) {
-  const Tile t = decode_tile(table, tb, it, MODE == MODE_DW, p.M, TILE_N);
+  // The list takes `rounds` full rounds of the XCD's workgroups plus `tail` tiles.  When
+  // the tail would leave at least half of the workgroups idle, each tail tile is cut
+  // along k into `split` chunks that run side by side; the chunks leave fp32 partial
+  // tiles in global memory and the workgroup that arrives last adds them up in chunk
+  // order (so the result does not depend on the order of arrival) and runs the epilogue.
+  // Only the row-segmented products do this: their tiles all have the same k range.
+  const int slot = blockIdx.x / kXcds;
+  const int rounds = tb.total / slots, tail = tb.total - rounds * slots;
+  int split = 1;
+  if (MODE != MODE_DW && p.partial != nullptr && tail > 0 && 2 * tail <= slots) {
+    const int kts = (p.K + BK - 1) / BK * (MODE == MODE_DX ? 2 : 1);
+    split = max(1, min(min(slots / tail, kMaxSplit), kts / kMinSplitKt));
+  }
+  const int my_tiles = rounds + (slot < tail * split ? 1 : 0);
+  for (int round = 0; round < my_tiles; ++round) {
+  const bool parted = split > 1 && round == rounds;
+  const int tail_tile = parted ? slot % tail : slot;
+  const int chunk = parted ? slot / tail : 0;
+  const Tile t = decode_tile(table, tb, round * slots + tail_tile, MODE == MODE_DW, p.M, TILE_N);
 
   // contraction range and per-expert operand bases
   const int k_begin = MODE == MODE_DW ? t.k_begin : 0, k_end = MODE == MODE_DW ? t.k_end : p.K;
@@ -308,6 +331,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   const int phases = MODE == MODE_DX ? 2 : 1;
   const int kt_per_phase = (k_end - k_begin + BK - 1) / BK;
   const int n_kt = kt_per_phase * phases;
+  const int kt_lo = parted ? chunk * n_kt / split : 0, kt_hi = parted ? (chunk + 1) * n_kt / split : n_kt;
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm = wave >> 1, wn = wave & 1;  // 4 x 2 wavefronts, 64 x 128 outputs each
@@ -351,7 +375,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     if (MODE == MODE_DX && ph > 1) ph = 1;
     const int k0 = k_begin + (kt - ph * kt_per_phase) * BK;
     KTile q;
-    q.k_left = kt < n_kt ? k_end - k0 : 0;
+    q.k_left = kt < kt_hi ? k_end - k0 : 0;
     const bf16_t* A = ph == 0 ? p.A1 : p.A2;
     const bf16_t* B = (MODE == MODE_DX && ph == 1) ? B2 : B1;
     q.a = make_rsrc(A_TRANS ? A + (long)k0 * p.lda + t.m0 : A + (long)t.m0 * p.lda + k0);
@@ -383,20 +407,20 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   const std::integral_constant<int, 1> c1;
 
   {
-    const KTile q0 = ktile(0);
+    const KTile q0 = ktile(kt_lo);
     static_for<kPieces>([&](auto J) { load_a(q0, J); });
     static_for<kPieces>([&](auto J) { load_b(q0, J); });
     static_for<kPieces>([&](auto J) { store_piece<A_TRANS>(smem, ra[J], J); });
     static_for<kPieces>([&](auto J) { store_piece<B_TRANS>(smem + kTileBytes, rb[J], J); });
-    const KTile q1 = ktile(1);
+    const KTile q1 = ktile(kt_lo + 1);
     static_for<kPieces>([&](auto J) { load_a(q1, J); });
     static_for<kPieces>([&](auto J) { load_b(q1, J); });
   }
   __syncthreads();
   static_for<6>([&](auto F) { read_frag(c0, F, 0, 0); });
 
-  for (int kt = 0; kt < n_kt; ++kt) {
-    const int stage = kt & 1;
+  for (int kt = kt_lo; kt < kt_hi; ++kt) {
+    const int stage = (kt - kt_lo) & 1;
     char* next = smem + ((stage ^ 1) * 2) * kTileBytes;
     const KTile q2 = ktile(kt + 2);
     __builtin_amdgcn_sched_barrier(0);
@@ -442,6 +466,49 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     });
   }
   __syncthreads();
+
+  if (parted) {
+    // Leave this chunk's partial tile (lane-major, 16 bytes per lane and store), then
+    // count the arrival; all but the last workgroup of the tile are done.
+    const size_t tile_f4 = kPartialBytes / 16;
+    float4* mine = (float4*)p.partial + (size_t)blockIdx.x * tile_f4;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          mine[((i * 4 + j) * 4 + q) * kMfmaThreads + threadIdx.x] =
+              make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int32_t* counter = p.counters + tail_tile * kXcds + xcd;
+      const int before = atomicAdd(counter, 1);
+      if (before == split - 1) *counter = 0;  // everyone has arrived: ready for the next launch
+      table[5] = before;
+    }
+    __syncthreads();
+    if (table[5] != split - 1) break;  // a split tile is always a workgroup's last
+    __threadfence();
+#pragma unroll 1
+    for (int c = 0; c < split; ++c) {
+      const float4* part = (const float4*)p.partial + (size_t)((c * tail + tail_tile) * kXcds + xcd) * tile_f4;
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const float4 v = part[((i * 4 + j) * 4 + q) * kMfmaThreads + threadIdx.x];
+            if (c == 0) {
+              acc[i][j][4 * q] = v.x; acc[i][j][4 * q + 1] = v.y; acc[i][j][4 * q + 2] = v.z; acc[i][j][4 * q + 3] = v.w;
+            } else {
+              acc[i][j][4 * q] += v.x; acc[i][j][4 * q + 1] += v.y; acc[i][j][4 * q + 2] += v.z; acc[i][j][4 * q + 3] += v.w;
+            }
+          }
+    }
+  }
 
   // ---- epilogue.  Accumulator element r of block (i, j) is row i*32 + (r/4)*8 +
   // (lane/32)*4 + r%4, column j*32 + lane%32 of the wavefront's 64x128 part.  Each
@@ -525,6 +592,7 @@ static int persistent_blocks(int max_tiles) {
       n = 256;
     cus = n / kXcds * kXcds;
     if (cus < kXcds) cus = kXcds;
+    if (cus > kMaxPersistent) cus = kMaxPersistent;
   }
   const int want = (max_tiles + kXcds - 1) / kXcds * kXcds;
   return want < cus ? want : cus;
@@ -544,16 +612,34 @@ static int32_t launch_mfma(const GemmParams& p, int max_tiles, KernelId id, hipS
   return DYNMO_OK;
 }
 
+// Scratch behind the split last round: the partial tiles, then the arrival counters.
+size_t ffn_mfma_scratch_bytes() { return kMaxPersistent * kPartialBytes + kMaxPersistent * sizeof(int32_t); }
+
+__global__ void zero_counters_kernel(int32_t* counters) { counters[threadIdx.x] = 0; }
+
+// The counters must be zero before the first launch of a call; each launch leaves them zero.
+static int32_t attach_scratch(GemmParams* p, void* scratch, bool clear, hipStream_t st) {
+  p->partial = (float*)scratch;
+  p->counters = (int32_t*)((char*)scratch + kMaxPersistent * kPartialBytes);
+  if (clear) {
+    zero_counters_kernel<<<dim3(1), dim3(kMaxPersistent), 0, st>>>(p->counters);
+    DYNMO_LAUNCH_CHECK();
+  }
+  return DYNMO_OK;
+}
+
 bool ffn_mfma_supported(const dynmo_desc* d) {
   return d->dtype == DYNMO_BF16 && d->H % 8 == 0 && d->F % 8 == 0 &&
          (int64_t)max_m_tiles(d, BM) * ((d->F + 127) / 128) < (1 << 30);
 }
 
 int32_t ffn_fwd_mfma(const dynmo_desc* d, const void* x_p, const int32_t* seg, const void* Wg, const void* Wu,
-                     const void* Wd, void* y_p, void* G, void* U, void* A, hipStream_t st) {
+                     const void* Wd, void* y_p, void* G, void* U, void* A, void* scratch, hipStream_t st) {
   const int mt = max_m_tiles(d, BM);
   const long FH = (long)d->F * d->H;
   GemmParams p = {};
+  int32_t rc = attach_scratch(&p, scratch, true, st);
+  if (rc) return rc;
   p.seg = seg;
   p.E = d->E;
   // G, U, A = gate/up projections
@@ -569,10 +655,11 @@ int32_t ffn_fwd_mfma(const dynmo_desc* d, const void* x_p, const int32_t* seg, c
   p.C1 = (bf16_t*)U;
   p.C2 = (bf16_t*)A;
   p.ldc = d->F;
-  int32_t rc = launch_mfma<MODE_GATEUP>(p, mt * ((d->F + 127) / 128), K_FFN_GATEUP, st);
+  rc = launch_mfma<MODE_GATEUP>(p, mt * ((d->F + 127) / 128), K_FFN_GATEUP, st);
   if (rc) return rc;
   // Y = A Wd^T
   GemmParams q = {};
+  attach_scratch(&q, scratch, false, st);
   q.seg = seg;
   q.E = d->E;
   q.N = d->H;
@@ -589,13 +676,14 @@ int32_t ffn_fwd_mfma(const dynmo_desc* d, const void* x_p, const int32_t* seg, c
 
 int32_t ffn_bwd_mfma(const dynmo_desc* d, const void* dy_p, const void* x_p, const void* G, const void* U,
                      const int32_t* seg, const void* Wg, const void* Wu, const void* Wd, void* dx_p, void* dWg,
-                     void* dWu, void* dWd, void* dG, void* dU, void* A, hipStream_t st) {
+                     void* dWu, void* dWd, void* dG, void* dU, void* A, void* scratch, hipStream_t st) {
   const int mt = max_m_tiles(d, BM);
   const long FH = (long)d->F * d->H;
   const int tH = (d->H + BN - 1) / BN, tF = (d->F + BN - 1) / BN;
   int32_t rc;
   {  // dA = dY Wd, epilogue -> A, dG, dU
     GemmParams p = {};
+    if ((rc = attach_scratch(&p, scratch, true, st))) return rc;
     p.seg = seg;
     p.E = d->E;
     p.N = d->F;
@@ -615,6 +703,7 @@ int32_t ffn_bwd_mfma(const dynmo_desc* d, const void* dy_p, const void* x_p, con
   }
   {  // dX = dG Wg + dU Wu
     GemmParams p = {};
+    attach_scratch(&p, scratch, false, st);
     p.seg = seg;
     p.E = d->E;
     p.N = d->H;
