@@ -122,7 +122,10 @@ size_t dynmo_grouped_ffn_fwd_workspace_bytes(const dynmo_desc* d);
 /* The per-token workload c_e of Sec. 2.1 (c_i of Sec. 2.5 / 2.6): for the rows of
  * each expert segment, G = X Wg[e]^T, U = X Wu[e]^T, A = silu(G) * U, Y = A Wd[e]^T.
  * x_p [T*k,H], seg_offsets [E+1], weights -> y_p [T*k,H]; G_save, U_save [T*k,F]
- * are kept for the backward pass. */
+ * are kept for the backward pass.  The workspace holds A and, for bf16, 64 MiB of
+ * fp32 partial tiles (a last, sparsely filled round of output tiles is split along
+ * the contraction and summed in a fixed order, so results are reproducible); its
+ * contents are scratch: two calls that overlap in time need separate workspaces. */
 int32_t dynmo_grouped_ffn_fwd(const dynmo_desc* d, const void* x_p, const int32_t* seg_offsets, const void* Wg,
                               const void* Wu, const void* Wd, void* y_p, void* G_save, void* U_save,
                               void* workspace, size_t workspace_bytes, void* stream);

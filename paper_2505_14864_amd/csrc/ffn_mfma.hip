@@ -49,9 +49,10 @@ constexpr int kEpWaveBytes = 32 * kEpPitch * 4;  // one 32-row band per wavefron
 constexpr int kXcds = 8;
 constexpr int kGroupN = 8;                   // column tiles that run side by side in one XCD
 constexpr int kMaxPersistent = 256;          // persistent workgroups per launch (one per compute unit)
-constexpr int kMaxSplit = 8;                 // most k chunks a tile of the last, partly filled round is cut into
-constexpr int kMinSplitKt = 8;               // ... each at least this many k tiles long
-constexpr size_t kPartialBytes = (size_t)BM * BN * 4;  // one workgroup's fp32 partial tile
+constexpr int kMinSplitKt = 16;              // a k chunk of a split tile is at least this many k tiles long
+constexpr int kMaxSplitTiles = kMaxPersistent / 2;     // tiles of a last round that is worth splitting
+constexpr size_t kPartialFloats = (size_t)BM * BN;     // one workgroup's fp32 partial tile
+constexpr int kSplitHdrInts = 4 + 4 * kMaxSplitTiles;  // {split, patches, slots, tiles} + {m0, m_end, n0, -} per tile
 
 static_assert(256 * kPitchK == 64 * kPitchT, "both tile layouts must have the same size");
 static_assert((kMfmaThreads / 64) * kEpWaveBytes <= kLdsBytes, "epilogue patches must fit in the staging buffers");
@@ -77,8 +78,7 @@ struct GemmParams {
   long ldc;
   const bf16_t* G;
   const bf16_t* U;
-  float* partial;     // kMaxPersistent partial tiles for the split last round, or nullptr (never split)
-  int32_t* counters;  // kMaxPersistent arrival counters, zero on entry, left zero on exit
+  float* partial;     // kMaxPersistent fp32 partial tiles, then kSplitHdrInts ints (modes that may split k)
 };
 
 // ---- global -> registers -> LDS staging ---------------------------------------
@@ -197,14 +197,15 @@ struct Tile {
 // its runs expert by expert as one flat list.
 struct TileTable {
   int nt;     // column tiles (same for all experts)
-  int total;  // tiles in this XCD's list
+  int total;  // tiles in the list decode_tile() indexes: the whole list for the row-segmented
+              // products, this XCD's list for the others
 };
 
 constexpr int kTableStride = 8;  // ints per expert in the LDS table
 // Per expert e, at table[kTableStride*e ..]: first row, end row, row tiles, number of
-// tiles of experts 0..e in this XCD's list, first tile of this XCD's run inside the
-// expert.  Built by the first wavefront into LDS (kept there so that it costs no
-// registers during the main loop); callers synchronise before reading it.
+// tiles of experts 0..e in the list, and what to add to a list position to get the tile
+// index inside the expert.  Built by the first wavefront into LDS (kept there so that
+// it costs no registers during the main loop); callers synchronise before reading it.
 __device__ __forceinline__ TileTable make_tile_table(int* table, const int32_t* __restrict__ seg, int E, bool dw, int M,
                                                      int N, int tile_n, int xcd) {
   const int lane = threadIdx.x & 63;
@@ -225,17 +226,10 @@ __device__ __forceinline__ TileTable make_tile_table(int* table, const int32_t* 
     }
     return v;
   };
-  int run_off, run_len;
+  int run_off = 0, run_len = n;
   if (dw) {
     run_off = (int)((long)n * xcd / kXcds);
     run_len = (int)((long)n * (xcd + 1) / kXcds) - run_off;
-  } else {
-    const int incl = scan(n);
-    const int all = __builtin_amdgcn_readlane(incl, 63);
-    const int per = (all + kXcds - 1) / kXcds;
-    const int lo = max(xcd * per, incl - n), hi = min(min((xcd + 1) * per, all), incl);
-    run_off = lo - (incl - n);
-    run_len = max(hi - lo, 0);
   }
   const int cum = scan(run_len);
   tb.total = __builtin_amdgcn_readlane(cum, 63);
@@ -250,7 +244,7 @@ __device__ __forceinline__ TileTable make_tile_table(int* table, const int32_t* 
   return tb;
 }
 
-// pos = position in this XCD's list
+// pos = position in the list
 __device__ __forceinline__ Tile decode_tile(const int* table, const TileTable& tb, int pos, bool dw, int M, int tile_n) {
   const int lane = threadIdx.x & 63;
   const unsigned long long mask = __ballot(table[kTableStride * lane + 3] > pos);
@@ -304,25 +298,46 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   // before the younger one; a higher priority for the younger wavefronts evens that
   // out (measured: a few percent).
   if (threadIdx.x >= kMfmaThreads / 2) __builtin_amdgcn_s_setprio(1);
-  // The list takes `rounds` full rounds of the XCD's workgroups plus `tail` tiles.  When
-  // the tail would leave at least half of the workgroups idle, each tail tile is cut
-  // along k into `split` chunks that run side by side; the chunks leave fp32 partial
-  // tiles in global memory and the workgroup that arrives last adds them up in chunk
-  // order (so the result does not depend on the order of arrival) and runs the epilogue.
-  // Only the row-segmented products do this: their tiles all have the same k range.
+  // Who runs what.  Products that contract over an expert's rows: the XCD's own list,
+  // one tile per workgroup and round.  Row-segmented products: XCD x takes the x-th
+  // contiguous eighth of the whole list.  If the last round of the grid would leave at
+  // least half of the XCDs idle (`patches` XCD-sized patches of tiles, 2 * patches <= 8),
+  // those last tiles are taken out of the eighths and each patch is run by `split` XCDs
+  // at once, every one on its own chunk of the k range: a patch keeps the operand
+  // sharing of an ordinary round.  The chunks leave fp32 partial tiles in global memory,
+  // which a second small kernel adds up in chunk order and converts.
+  constexpr bool CAN_SPLIT = MODE == MODE_DOWN || MODE == MODE_DX;
   const int slot = blockIdx.x / kXcds;
-  const int rounds = tb.total / slots, tail = tb.total - rounds * slots;
-  int split = 1;
-  if (MODE != MODE_DW && p.partial != nullptr && tail > 0 && 2 * tail <= slots) {
-    const int kts = (p.K + BK - 1) / BK * (MODE == MODE_DX ? 2 : 1);
-    split = max(1, min(min(slots / tail, kMaxSplit), kts / kMinSplitKt));
+  int first = 0, mine = tb.total;  // this XCD's run of the list
+  int split = 1, patches = 0, tail_tiles = 0;
+  if (MODE != MODE_DW) {
+    const int all = tb.total;
+    if (CAN_SPLIT && p.partial != nullptr) {
+      tail_tiles = all % (int)gridDim.x;
+      patches = (tail_tiles + slots - 1) / slots;
+      const int kts = (p.K + BK - 1) / BK * (MODE == MODE_DX ? 2 : 1);
+      if (tail_tiles > 0 && 2 * patches <= kXcds) split = max(1, min(kXcds / patches, kts / kMinSplitKt));
+      if (split == 1) tail_tiles = 0;
+    }
+    const int per = (all - tail_tiles + kXcds - 1) / kXcds;
+    first = min(xcd * per, all - tail_tiles);
+    mine = min(per, all - tail_tiles - first);
   }
-  const int my_tiles = rounds + (slot < tail * split ? 1 : 0);
-  for (int round = 0; round < my_tiles; ++round) {
-  const bool parted = split > 1 && round == rounds;
-  const int tail_tile = parted ? slot % tail : slot;
-  const int chunk = parted ? slot / tail : 0;
-  const Tile t = decode_tile(table, tb, round * slots + tail_tile, MODE == MODE_DW, p.M, TILE_N);
+  const int my_rounds = slot < mine ? (mine - slot + slots - 1) / slots : 0;
+  const int tail_tile = (xcd / split) * slots + slot;  // index among the split tiles
+  const bool has_part = split > 1 && tail_tile < tail_tiles;
+  if (CAN_SPLIT && p.partial != nullptr && blockIdx.x == 0 && threadIdx.x == 0) {
+    int32_t* hdr = (int32_t*)(p.partial + kMaxPersistent * kPartialFloats);
+    hdr[0] = split;
+    hdr[1] = patches;
+    hdr[2] = slots;
+    hdr[3] = tail_tiles;
+  }
+  for (int round = 0; round < my_rounds + (has_part ? 1 : 0); ++round) {
+  const bool parted = CAN_SPLIT && round == my_rounds;
+  const int chunk = parted ? xcd % split : 0;
+  const Tile t = decode_tile(table, tb, parted ? tb.total - tail_tiles + tail_tile : first + round * slots + slot,
+                             MODE == MODE_DW, p.M, TILE_N);
 
   // contraction range and per-expert operand bases
   const int k_begin = MODE == MODE_DW ? t.k_begin : 0, k_end = MODE == MODE_DW ? t.k_end : p.K;
@@ -467,49 +482,6 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   }
   __syncthreads();
 
-  if (parted) {
-    // Leave this chunk's partial tile (lane-major, 16 bytes per lane and store), then
-    // count the arrival; all but the last workgroup of the tile are done.
-    const size_t tile_f4 = kPartialBytes / 16;
-    float4* mine = (float4*)p.partial + (size_t)blockIdx.x * tile_f4;
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-          mine[((i * 4 + j) * 4 + q) * kMfmaThreads + threadIdx.x] =
-              make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      int32_t* counter = p.counters + tail_tile * kXcds + xcd;
-      const int before = atomicAdd(counter, 1);
-      if (before == split - 1) *counter = 0;  // everyone has arrived: ready for the next launch
-      table[5] = before;
-    }
-    __syncthreads();
-    if (table[5] != split - 1) break;  // a split tile is always a workgroup's last
-    __threadfence();
-#pragma unroll 1
-    for (int c = 0; c < split; ++c) {
-      const float4* part = (const float4*)p.partial + (size_t)((c * tail + tail_tile) * kXcds + xcd) * tile_f4;
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const float4 v = part[((i * 4 + j) * 4 + q) * kMfmaThreads + threadIdx.x];
-            if (c == 0) {
-              acc[i][j][4 * q] = v.x; acc[i][j][4 * q + 1] = v.y; acc[i][j][4 * q + 2] = v.z; acc[i][j][4 * q + 3] = v.w;
-            } else {
-              acc[i][j][4 * q] += v.x; acc[i][j][4 * q + 1] += v.y; acc[i][j][4 * q + 2] += v.z; acc[i][j][4 * q + 3] += v.w;
-            }
-          }
-    }
-  }
-
   // ---- epilogue.  Accumulator element r of block (i, j) is row i*32 + (r/4)*8 +
   // (lane/32)*4 + r%4, column j*32 + lane%32 of the wavefront's 64x128 part.  Each
   // wavefront passes one 32-row band at a time through its own LDS patch (fp32,
@@ -520,6 +492,14 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   bf16_t* __restrict__ C0 = p.C0 + (MODE == MODE_DW ? (long)t.e * p.M * p.N : 0);
   bf16_t* __restrict__ C1 = p.C1;
   bf16_t* __restrict__ C2 = p.C2;
+  // a k chunk of a split tile leaves fp32 sums, row-major in tile coordinates
+  float* __restrict__ part = CAN_SPLIT ? p.partial + (size_t)blockIdx.x * kPartialFloats : nullptr;
+  if (CAN_SPLIT && parted && chunk == 0 && threadIdx.x == 0) {
+    int32_t* desc = (int32_t*)(p.partial + kMaxPersistent * kPartialFloats) + 4 + 4 * tail_tile;
+    desc[0] = t.m0;
+    desc[1] = t.m_end;
+    desc[2] = t.n0;
+  }
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     if (i > 0) __syncthreads();
@@ -560,7 +540,11 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
         float v[8];
 #pragma unroll
         for (int q = 0; q < 8; ++q) v[q] = ep[rl * kEpPitch + c0 + q];
-        if (MODE == MODE_DA) {
+        if (CAN_SPLIT && parted) {
+          float* dst = part + (wm * 64 + i * 32 + rl) * BN + wn * 128 + c0;
+          *(float4*)dst = make_float4(v[0], v[1], v[2], v[3]);
+          *(float4*)(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
+        } else if (MODE == MODE_DA) {
           if (ok) {
             float g[8], u[8], a_[8], dg[8], du[8];
             unpack16<bf16_t>(*(const u32x4*)(Gs + o), g);
@@ -580,6 +564,45 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   __syncthreads();  // the LDS patches are reused by the next tile's staging
   }  // tile loop
 }
+
+// Second pass of a product whose last round was split along k: adds the chunks'
+// partial tiles in chunk order, converts and stores.  One workgroup per quarter tile;
+// the grid covers the most tiles a split can have, and workgroups beyond what the first
+// pass recorded in the header return at once.
+__global__ __launch_bounds__(256) void ffn_split_reduce_kernel(const float* __restrict__ partial, bf16_t* __restrict__ C,
+                                                               long ldc, int N) {
+  const int32_t* hdr = (const int32_t*)(partial + kMaxPersistent * kPartialFloats);
+  const int split = hdr[0], slots = hdr[2], tiles = hdr[3];
+  const int u = blockIdx.x >> 2, quarter = blockIdx.x & 3;
+  if (split <= 1 || u >= tiles) return;
+  const int32_t* desc = hdr + 4 + 4 * u;
+  const int m0 = desc[0], m_end = desc[1], n0 = desc[2];
+  // chunk c of split tile u was run by workgroup (u % slots) of XCD (u / slots) * split + c
+  const float* src = partial + (size_t)((u % slots) * kXcds + (u / slots) * split) * kPartialFloats;
+  const int col = (threadIdx.x & 63) * 4;
+#pragma unroll 4
+  for (int it = 0; it < 16; ++it) {
+    const int rl = quarter * 64 + it * 4 + (threadIdx.x >> 6);
+    float4 sum = *(const float4*)(src + rl * BN + col);
+    for (int c = 1; c < split; ++c) {
+      const float4 v = *(const float4*)(src + (size_t)c * kPartialFloats + rl * BN + col);
+      sum.x += v.x;
+      sum.y += v.y;
+      sum.z += v.z;
+      sum.w += v.w;
+    }
+    const int row = m0 + rl;
+    if (row < m_end && n0 + col < N) {
+      uint2 o;
+      o.x = pack_bf16x2(sum.x, sum.y);
+      o.y = pack_bf16x2(sum.z, sum.w);
+      *(uint2*)(C + (long)row * ldc + n0 + col) = o;
+    }
+  }
+}
+
+// Scratch of the products that may split k: the partial tiles, then the header.
+size_t ffn_mfma_scratch_bytes() { return kMaxPersistent * kPartialFloats * 4 + kSplitHdrInts * sizeof(int32_t); }
 
 // Workgroups are persistent: one per compute unit (the LDS and register use allow
 // no more), capped by the number of tiles the shapes can produce.
@@ -607,22 +630,14 @@ static int32_t launch_mfma(const GemmParams& p, int max_tiles, KernelId id, hipS
     attr_set = true;
   }
   if (max_tiles <= 0) return DYNMO_OK;
-  const int blocks = persistent_blocks(max_tiles);
-  DYNMO_TIMED_LAUNCH(id, st, ffn_mfma_kernel<MODE><<<dim3(blocks), dim3(kMfmaThreads), kLdsBytes + kTableBytes, st>>>(p));
-  return DYNMO_OK;
-}
-
-// Scratch behind the split last round: the partial tiles, then the arrival counters.
-size_t ffn_mfma_scratch_bytes() { return kMaxPersistent * kPartialBytes + kMaxPersistent * sizeof(int32_t); }
-
-__global__ void zero_counters_kernel(int32_t* counters) { counters[threadIdx.x] = 0; }
-
-// The counters must be zero before the first launch of a call; each launch leaves them zero.
-static int32_t attach_scratch(GemmParams* p, void* scratch, bool clear, hipStream_t st) {
-  p->partial = (float*)scratch;
-  p->counters = (int32_t*)((char*)scratch + kMaxPersistent * kPartialBytes);
-  if (clear) {
-    zero_counters_kernel<<<dim3(1), dim3(kMaxPersistent), 0, st>>>(p->counters);
+  // a product that may split k always brings every compute unit: few tiles is when it splits
+  const bool may_split = (MODE == MODE_DOWN || MODE == MODE_DX) && p.partial != nullptr;
+  const int blocks = persistent_blocks(may_split ? kMaxPersistent : max_tiles);
+  ProfScope prof(id, st);
+  ffn_mfma_kernel<MODE><<<dim3(blocks), dim3(kMfmaThreads), kLdsBytes + kTableBytes, st>>>(p);
+  DYNMO_LAUNCH_CHECK();
+  if (may_split) {
+    ffn_split_reduce_kernel<<<dim3(4 * kMaxSplitTiles), dim3(256), 0, st>>>(p.partial, p.C0, p.ldc, p.N);
     DYNMO_LAUNCH_CHECK();
   }
   return DYNMO_OK;
@@ -638,8 +653,6 @@ int32_t ffn_fwd_mfma(const dynmo_desc* d, const void* x_p, const int32_t* seg, c
   const int mt = max_m_tiles(d, BM);
   const long FH = (long)d->F * d->H;
   GemmParams p = {};
-  int32_t rc = attach_scratch(&p, scratch, true, st);
-  if (rc) return rc;
   p.seg = seg;
   p.E = d->E;
   // G, U, A = gate/up projections
@@ -655,11 +668,11 @@ int32_t ffn_fwd_mfma(const dynmo_desc* d, const void* x_p, const int32_t* seg, c
   p.C1 = (bf16_t*)U;
   p.C2 = (bf16_t*)A;
   p.ldc = d->F;
-  rc = launch_mfma<MODE_GATEUP>(p, mt * ((d->F + 127) / 128), K_FFN_GATEUP, st);
+  int32_t rc = launch_mfma<MODE_GATEUP>(p, mt * ((d->F + 127) / 128), K_FFN_GATEUP, st);
   if (rc) return rc;
   // Y = A Wd^T
   GemmParams q = {};
-  attach_scratch(&q, scratch, false, st);
+  q.partial = (float*)scratch;
   q.seg = seg;
   q.E = d->E;
   q.N = d->H;
@@ -683,7 +696,6 @@ int32_t ffn_bwd_mfma(const dynmo_desc* d, const void* dy_p, const void* x_p, con
   int32_t rc;
   {  // dA = dY Wd, epilogue -> A, dG, dU
     GemmParams p = {};
-    if ((rc = attach_scratch(&p, scratch, true, st))) return rc;
     p.seg = seg;
     p.E = d->E;
     p.N = d->F;
@@ -703,7 +715,7 @@ int32_t ffn_bwd_mfma(const dynmo_desc* d, const void* dy_p, const void* x_p, con
   }
   {  // dX = dG Wg + dU Wu
     GemmParams p = {};
-    attach_scratch(&p, scratch, false, st);
+    p.partial = (float*)scratch;
     p.seg = seg;
     p.E = d->E;
     p.N = d->H;
