@@ -31,6 +31,11 @@ def parse():
                     help="after the timed region, run one plain 1 GiB device copy (a known-size reference for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="tokens in the oracle's timed sample (0 = auto)")
+    ap.add_argument("--protocol", action="store_true",
+                    help="instead of the headline line: the full timing protocol (>= 10 warm-up and >= 50 timed "
+                         "repetitions, median and min per kernel, HBM-bound calls alone warm and cold, forward and "
+                         "forward+backward chains, uniform and adversarial routing, the box's own MFMA and copy "
+                         "ceilings); prints one JSON line")
     return ap.parse_args()
 
 
@@ -119,6 +124,10 @@ def main():
         if len(per_task) >= stage_split and stage_split > 0:
             B.dynmo_partition(per_task, stage_split)
         return rows, per_task
+
+    if a.protocol:
+        print(json.dumps(protocol(a, w, inp, dev, layers, Ws, step)))
+        return
 
     for _ in range(a.warmup):
         step()
@@ -219,6 +228,187 @@ def main():
         "input_generation_s": round(gen_s, 1),
     }
     print(json.dumps(out))
+
+
+def _stats(xs):
+    xs = sorted(xs)
+    return {"median_us": round(xs[len(xs) // 2] * 1e3, 2), "min_us": round(xs[0] * 1e3, 2), "reps": len(xs)}
+
+
+def protocol(a, w, inp, dev, layers, Ws, step):
+    """Timing protocol of the whole path and of each call (times in microseconds).
+    Durations of single kernels are the library's hipEvent pairs; chains are
+    bracketed by events on the same stream."""
+    import numpy as np
+    import torch
+    from paper_2505_14864_amd import binding as B
+    from paper_2505_14864_amd import workloads as wl
+    from paper_2505_14864_amd.layer import to_device
+
+    reps, warm = max(50, a.steps), max(10, a.warmup)
+    names = [B.dynmo_profile_kernel_name(i) for i in range(B.dynmo_profile_kernel_count())]
+    out = {"workload": "config %d: %s" % (a.config, w.name), "reps": reps, "warmup": warm}
+
+    def timed(fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1)
+
+    # ---- what this box reaches: MFMA issue with no memory traffic, streaming copy
+    sink = torch.empty(256 * 512, dtype=torch.float32, device="cuda")
+    flops = [0.0]
+
+    def mfma():
+        flops[0] = B.dynmo_peak_mfma_bf16(20000, sink)
+    mfma()
+    torch.cuda.synchronize()
+    t_mfma = min(timed(mfma) for _ in range(5))
+    evict = torch.empty(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB: four times the Infinity Cache
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    B.dynmo_peak_copy(evict, src)
+    t_copy = min(timed(lambda: B.dynmo_peak_copy(evict, src)) for _ in range(5))
+    small = 48 << 20  # bytes each way: the footprint of a config-2 row kernel
+    s_src, s_dst = src.view(torch.uint8)[:small], evict.view(torch.uint8)[small:2 * small]
+    t_small_warm = min(timed(lambda: B.dynmo_peak_copy(s_dst, s_src)) for _ in range(10))
+    t_small_cold = []
+    spare = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+    for _ in range(10):
+        spare.fill_(1.0)
+        t_small_cold.append(timed(lambda: B.dynmo_peak_copy(s_dst, s_src)))
+    meas_flops = flops[0] / (t_mfma * 1e-3)
+    meas_bw = 2.0 * src.numel() * 4 / (t_copy * 1e-3)
+    out["measured_peaks"] = {
+        "mfma_bf16_tflops": round(meas_flops / 1e12, 1), "mfma_vs_nominal": round(meas_flops / PEAK_BF16_FLOPS, 3),
+        "copy_1GiB_GBps": round(meas_bw / 1e9, 1), "copy_vs_nominal": round(meas_bw / PEAK_HBM_BPS, 3),
+        "copy_96MiB_warm_GBps": round(2.0 * small / (t_small_warm * 1e-3) / 1e9, 1),
+        "copy_96MiB_cold_GBps": round(2.0 * small / (sorted(t_small_cold)[5] * 1e-3) / 1e9, 1)}
+    del src
+
+    def cold():
+        spare.fill_(1.0)
+
+    # ---- every kernel inside the forward+backward chain, one repetition at a time
+    for _ in range(warm):
+        step()
+    torch.cuda.synchronize()
+    per = {n: [] for n in names}
+    chain, rows = [], 0
+    B.dynmo_profile_enable(True)
+    for _ in range(reps):
+        B.dynmo_profile_reset()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        rows, _ = step()
+        e1.record()
+        e1.synchronize()
+        chain.append(e0.elapsed_time(e1))
+        for i, n in enumerate(names):
+            ms, cnt = B.dynmo_profile_read(i)
+            if cnt:
+                per[n].append(ms)  # all launches of the role in one pass (one per layer)
+    B.dynmo_profile_enable(False)
+    kern = {}
+    L = len(layers)
+    for n, xs in per.items():
+        if not xs:
+            continue
+        st = _stats(xs)
+        work = kernel_work(n, w, rows, w.T) if L == 1 else None
+        if work:
+            peak = {"mfma": PEAK_BF16_FLOPS if w.dtype == "bf16" else PEAK_FP32_FLOPS, "hbm": PEAK_HBM_BPS}[work[0]]
+            meas = {"mfma": meas_flops, "hbm": meas_bw}[work[0]]
+            rate = work[1] / (st["median_us"] * 1e-6)
+            st.update(bound=work[0], frac_nominal=round(rate / peak, 4))
+            if w.dtype == "bf16" or work[0] == "hbm":
+                st["frac_measured"] = round(rate / meas, 4)
+        kern[n] = st
+    out["in_chain"] = kern
+    fb = _stats(chain)
+    fb["routed_rows_per_s"] = round(rows / (fb["median_us"] * 1e-6), 1)
+    out["fwd_bwd_chain"] = fb
+
+    # ---- the forward chain alone
+    def fwd_only():
+        x = dev["x"]
+        for i, layer in enumerate(layers):
+            if w.mode == "moe":
+                layer.route_topk(dev["logits"])
+            elif w.mode == "mod":
+                layer.route_capacity(dev["scores"], w.cap)
+            else:
+                layer.route_active(dev["exit_layer"], i + 1)
+            x = layer.forward(x, *Ws[i])
+    for _ in range(3):
+        fwd_only()
+    out["fwd_chain"] = _stats([timed(fwd_only) for _ in range(reps)])
+
+    # ---- the HBM-bound calls alone, warm (back to back) and cold (caches evicted first)
+    if L == 1:
+        l0 = layers[0]
+        d = l0.d
+        base = dev["x"] if l0.residual else None
+        dbase = dev["dout"] if l0.residual else None
+        calls = {
+            "permute_rows": lambda: B.dynmo_permute(d, dev["x"], l0.expert_idx, l0.x_p, l0.seg_offsets, l0.src_slot,
+                                                    l0.dst_pos, l0.ws_permute),
+            "combine": lambda: B.dynmo_combine(d, l0.y_p, l0.dst_pos, l0.gate_w, base, l0.out),
+            "combine_bwd": lambda: B.dynmo_combine_bwd(d, dev["dout"], l0.y_p, l0.dst_pos, l0.gate_w, l0.dy_p, l0.dgate),
+            "permute_bwd": lambda: B.dynmo_permute_bwd(d, l0.dx_p, l0.dst_pos, dbase, l0.dx),
+        }
+        alone = {}
+        B.dynmo_profile_enable(True)
+        for n, fn in calls.items():
+            idx = names.index(n)
+            bytes_ = kernel_work(n, w, rows, w.T)[1]
+            ent = {}
+            for label, pre in (("warm", None), ("cold", cold)):
+                xs = []
+                for _ in range(reps):
+                    if pre:
+                        pre()
+                    B.dynmo_profile_reset()
+                    fn()
+                    xs.append(B.dynmo_profile_read(idx)[0])
+                st = _stats(xs)
+                rate = bytes_ / (st["median_us"] * 1e-6)
+                st.update(GBps=round(rate / 1e9, 1), frac_nominal=round(rate / PEAK_HBM_BPS, 4),
+                          frac_measured_copy=round(rate / meas_bw, 4))
+                ent[label] = st
+            ent["algorithmic_bytes"] = bytes_
+            alone[n] = ent
+        B.dynmo_profile_enable(False)
+        out["hbm_calls_alone"] = alone
+
+    # ---- other routing histograms at the same shape (reported, not the headline)
+    if w.mode == "moe":
+        variants = {}
+        base_logits = inp["logits"] - wl.expert_bias(w)[None, :]
+        adv = inp["logits"].copy()
+        adv[:, 0] += 6.0          # everybody's first choice: T rows, the most one expert can get
+        adv[:, w.E - 1] -= 40.0   # nobody's choice: an empty expert
+        keep = dev["logits"]
+        for label, lg in (("uniform_routing", base_logits), ("adversarial_histogram", adv)):
+            dev["logits"] = to_device(np.ascontiguousarray(lg.astype(np.float32)))
+            for _ in range(3):
+                step()
+            xs = []
+            for _ in range(max(10, reps // 5)):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                r, _ = step()
+                e1.record()
+                e1.synchronize()
+                xs.append(e0.elapsed_time(e1))
+            st = _stats(xs)
+            counts, _ = layers[0].load()
+            st.update(routed_rows_per_s=round(r / (st["median_us"] * 1e-6), 1), counts=[int(c) for c in counts])
+            variants[label] = st
+        dev["logits"] = keep
+        out["routing_variants"] = variants
+    return out
 
 
 def cpu_baseline(w, inp, sample_tokens):

@@ -200,6 +200,20 @@ int32_t dynmo_profile_kernel_count(void);
 const char* dynmo_profile_kernel_name(int32_t id);
 int32_t dynmo_profile_read(int32_t id, double* total_ms_host, int64_t* launches_host);
 
+/* ---- what the device can reach ---------------------------------------------- */
+
+/* Measurement aids, not part of the method: reference kernels whose duration the
+ * caller times on `stream` to get the box's own ceilings next to the data-sheet ones.
+ *
+ * dynmo_peak_mfma_bf16: 256 workgroups of eight wavefronts issue `iters` x 8
+ * v_mfma_f32_32x32x16_bf16 each on register operands; *flops_host (HOST) gets the
+ * flop count of the launch.  sink: DEVICE, 256 * 512 floats, overwritten.
+ *
+ * dynmo_peak_copy: plain streaming copy of `bytes` (a multiple of 16; DEVICE
+ * pointers, 16-byte aligned, not overlapping): reads `bytes`, writes `bytes`. */
+int32_t dynmo_peak_mfma_bf16(int32_t iters, float* sink, double* flops_host, void* stream);
+int32_t dynmo_peak_copy(void* dst, const void* src, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

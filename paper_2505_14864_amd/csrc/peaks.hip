@@ -1,0 +1,72 @@
+// Two reference kernels that measure what the device can reach, for judging the
+// library's kernels against the machine rather than against data-sheet numbers:
+// a register-resident bf16 MFMA loop (no memory traffic at all) and a plain
+// streaming copy (16 bytes per lane, four independent loads in flight).
+#include "common.h"
+
+namespace dynmo {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+constexpr int kPeakBlocks = 256, kPeakThreads = 512, kPeakAcc = 8;
+
+// Eight wavefronts per workgroup (two per SIMD), eight independent accumulator
+// blocks per wavefront: every MFMA has its operands in registers and depends only
+// on the MFMA issued eight instructions earlier.
+__global__ __launch_bounds__(kPeakThreads, 1) void peak_mfma_kernel(float* __restrict__ sink, int iters) {
+  bf16x8_t a, b;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    a[j] = (__bf16)(0.001f * (threadIdx.x & 63) + j);
+    b[j] = (__bf16)(0.5f * j);
+  }
+  f32x16_t acc[kPeakAcc];
+#pragma unroll
+  for (int i = 0; i < kPeakAcc; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < kPeakAcc; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < kPeakAcc; ++i) s += acc[i][0];
+  sink[(size_t)blockIdx.x * kPeakThreads + threadIdx.x] = s;
+}
+
+__global__ __launch_bounds__(256) void peak_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x;
+  u32x4 v[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (i + u * 256 < n) v[u] = src[i + u * 256];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (i + u * 256 < n) dst[i + u * 256] = v[u];
+}
+
+}  // namespace dynmo
+
+using namespace dynmo;
+
+extern "C" int32_t dynmo_peak_mfma_bf16(int32_t iters, float* sink, double* flops_host, void* stream) {
+  if (iters <= 0 || !sink || !flops_host) return DYNMO_EINVAL;
+  peak_mfma_kernel<<<dim3(kPeakBlocks), dim3(kPeakThreads), 0, (hipStream_t)stream>>>(sink, iters);
+  DYNMO_LAUNCH_CHECK();
+  // one 32x32x16 MFMA = 2 * 32 * 32 * 16 flop per wavefront
+  *flops_host = (double)kPeakBlocks * (kPeakThreads / 64) * (double)iters * kPeakAcc * 32768.0;
+  return DYNMO_OK;
+}
+
+extern "C" int32_t dynmo_peak_copy(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src || bytes % 16) return DYNMO_EINVAL;
+  const size_t n = bytes / 16;
+  if (n == 0) return DYNMO_OK;
+  if ((n + 1023) / 1024 > 0x7fffffffu) return DYNMO_EUNSUPPORTED;
+  peak_copy_kernel<<<dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, (hipStream_t)stream>>>((const u32x4*)src,
+                                                                                              (u32x4*)dst, n);
+  DYNMO_LAUNCH_CHECK();
+  return DYNMO_OK;
+}

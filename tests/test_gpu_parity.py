@@ -446,3 +446,22 @@ def test_bad_arguments_on_the_gpu():
     with pytest.raises(B.DynmoError) as e:
         B.dynmo_combine(d9, big, ei, torch.zeros((64, 2), device="cuda"), None, x)
     assert e.value.status == -2  # more than 8 slots
+
+
+def test_peak_reference_kernels():
+    """The two measurement aids: the copy moves the bytes, the MFMA loop reports its flops."""
+    say("peak reference kernels")
+    src = torch.arange(0, 1 << 20, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    assert B.dynmo_peak_copy(dst, src) == 4 << 20
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    tail_src, tail_dst = src[: 1028], torch.zeros(1028, dtype=torch.int32, device="cuda")  # not a multiple of the block
+    B.dynmo_peak_copy(tail_dst, tail_src)
+    torch.cuda.synchronize()
+    assert torch.equal(tail_dst, tail_src)
+    sink = torch.zeros(256 * 512, dtype=torch.float32, device="cuda")
+    flops = B.dynmo_peak_mfma_bf16(10, sink)
+    torch.cuda.synchronize()
+    assert flops == 256 * 8 * 10 * 8 * 32768.0
+    assert bool(torch.isfinite(sink).all())
