@@ -432,6 +432,28 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     static_for<kPieces>([&](auto J) { load_b(q1, J); });
   }
   __syncthreads();
+  // A wavefront whose 64 x 128 part lies wholly outside the valid rows or columns (the
+  // ragged last row tile of an expert, a narrow last column tile) only keeps up the
+  // staging: it moves its pieces and meets the barriers, but reads no fragments and
+  // issues no MFMAs, which leaves the SIMD and the LDS to the wavefronts that have work.
+  const int wave_u = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const bool has_work = t.m0 + (wave_u >> 1) * 64 < t.m_end &&
+                        (MODE == MODE_GATEUP ? t.n0 + (wave_u & 1) * 64 : t.n0 + (wave_u & 1) * 128) < n_end;
+  if (!has_work) {
+    for (int kt = kt_lo; kt < kt_hi; ++kt) {
+      char* next = smem + ((((kt - kt_lo) & 1) ^ 1) * 2) * kTileBytes;
+      const KTile q2 = ktile(kt + 2);
+      static_for<kPieces>([&](auto J) {
+        store_piece<A_TRANS>(next, ra[J], J);
+        load_a(q2, J);
+      });
+      static_for<kPieces>([&](auto J) {
+        store_piece<B_TRANS>(next + kTileBytes, rb[J], J);
+        load_b(q2, J);
+      });
+      __syncthreads();
+    }
+  } else {
   static_for<6>([&](auto F) { read_frag(c0, F, 0, 0); });
 
   for (int kt = kt_lo; kt < kt_hi; ++kt) {
@@ -480,6 +502,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
       __builtin_amdgcn_sched_barrier(0);
     });
   }
+  }  // has_work
   __syncthreads();
 
   // ---- epilogue.  Accumulator element r of block (i, j) is row i*32 + (r/4)*8 +
