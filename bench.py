@@ -30,6 +30,7 @@ def parse():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run one plain 1 GiB device copy (a known-size reference for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--protocol-text", default="", help="with --protocol: also write the result as a text table here")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="tokens in the oracle's timed sample (0 = auto)")
     ap.add_argument("--protocol", action="store_true",
                     help="instead of the headline line: the full timing protocol (>= 10 warm-up and >= 50 timed "
@@ -126,7 +127,11 @@ def main():
         return rows, per_task
 
     if a.protocol:
-        print(json.dumps(protocol(a, w, inp, dev, layers, Ws, step)))
+        res = protocol(a, w, inp, dev, layers, Ws, step)
+        if a.protocol_text:
+            with open(a.protocol_text, "w") as f:
+                f.write(protocol_text(res, a))
+        print(json.dumps(res))
         return
 
     for _ in range(a.warmup):
@@ -259,13 +264,19 @@ def protocol(a, w, inp, dev, layers, Ws, step):
 
     # ---- what this machine reaches: MFMA issue with no memory traffic, streaming copy
     sink = torch.empty(256 * 512, dtype=torch.float32, device="cuda")
+    operands = torch.randn(4096, dtype=torch.float32, device="cuda").to(torch.bfloat16)  # 8 KiB of N(0,1)
     flops = [0.0]
 
-    def mfma():
-        flops[0] = B.dynmo_peak_mfma_bf16(20000, sink)
+    def mfma(ops=None, iters=20000):
+        flops[0] = B.dynmo_peak_mfma_bf16(iters, sink, ops)
     mfma()
     torch.cuda.synchronize()
     t_mfma = min(timed(mfma) for _ in range(5))
+    # the same loop on random operands, long enough (about 0.3 s) for the clock to settle under the power it draws
+    mfma(operands)
+    t_rand = min(timed(lambda: mfma(operands, 600000)) for _ in range(2))
+    rand_flops = flops[0] / (t_rand * 1e-3)
+    mfma()
     evict = torch.empty(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB: four times the Infinity Cache
     src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
     B.dynmo_peak_copy(evict, src)
@@ -282,6 +293,8 @@ def protocol(a, w, inp, dev, layers, Ws, step):
     meas_bw = 2.0 * src.numel() * 4 / (t_copy * 1e-3)
     out["measured_peaks"] = {
         "mfma_bf16_tflops": round(meas_flops / 1e12, 1), "mfma_vs_nominal": round(meas_flops / PEAK_BF16_FLOPS, 3),
+        "mfma_bf16_random_operands_sustained_tflops": round(rand_flops / 1e12, 1),
+        "mfma_random_vs_nominal": round(rand_flops / PEAK_BF16_FLOPS, 3),
         "copy_1GiB_GBps": round(meas_bw / 1e9, 1), "copy_vs_nominal": round(meas_bw / PEAK_HBM_BPS, 3),
         "copy_96MiB_warm_GBps": round(2.0 * small / (t_small_warm * 1e-3) / 1e9, 1),
         "copy_96MiB_cold_GBps": round(2.0 * small / (sorted(t_small_cold)[5] * 1e-3) / 1e9, 1)}
@@ -324,6 +337,8 @@ def protocol(a, w, inp, dev, layers, Ws, step):
             st.update(bound=work[0], frac_nominal=round(rate / peak, 4))
             if w.dtype == "bf16" or work[0] == "hbm":
                 st["frac_measured"] = round(rate / meas, 4)
+            if w.dtype == "bf16" and work[0] == "mfma":
+                st["frac_measured_random_operands"] = round(rate / rand_flops, 4)
         kern[n] = st
     out["in_chain"] = kern
     fb = _stats(chain)
@@ -409,6 +424,58 @@ def protocol(a, w, inp, dev, layers, Ws, step):
         dev["logits"] = keep
         out["routing_variants"] = variants
     return out
+
+
+def protocol_text(d, a):
+    """The --protocol result as a table for reading."""
+    pct = lambda v: "%.1f%%" % (100 * v) if v is not None else "-"
+    L = ["Timing protocol, %s, one MI355X" % d["workload"],
+         "command: python bench.py --protocol --config %d --protocol-text <this file>" % a.config,
+         "%d warm-up passes, %d timed repetitions; times in microseconds." % (d["warmup"], d["reps"]),
+         "nominal = 2.5 PFLOP/s bf16 MFMA, 8 TB/s HBM; measured = this box's own ceilings from the library's two",
+         "reference kernels (dynmo_peak_mfma_bf16, dynmo_peak_copy).", ""]
+    m = d["measured_peaks"]
+    L += ["Measured ceilings of this box",
+          "  register-resident bf16 MFMA loop, fixed operands      : %8.1f TFLOP/s  (%s of nominal)" % (
+              m["mfma_bf16_tflops"], pct(m["mfma_vs_nominal"])),
+          "  the same loop on N(0,1) operands, 0.3 s sustained     : %8.1f TFLOP/s  (%s of nominal; the clock drops "
+          "under the power real data draws)" % (m["mfma_bf16_random_operands_sustained_tflops"],
+                                                 pct(m["mfma_random_vs_nominal"])),
+          "  streaming copy, 1 GiB each way                        : %8.1f GB/s     (%s of nominal)" % (
+              m["copy_1GiB_GBps"], pct(m["copy_vs_nominal"])),
+          "  streaming copy, 48 MiB each way                       : %8.1f GB/s back to back, %.1f GB/s after a "
+          "1 GiB cache-evicting fill" % (m["copy_96MiB_warm_GBps"], m["copy_96MiB_cold_GBps"]), ""]
+    L += ["Kernels inside the forward+backward chain (all launches of a role in one pass)",
+          "  %-16s %10s %10s  %-5s %9s %9s %12s" % ("kernel", "median", "min", "bound", "nominal", "measured",
+                                                   "random-data")]
+    for n, s in sorted(d["in_chain"].items(), key=lambda kv: -kv[1]["median_us"]):
+        L.append("  %-16s %10.2f %10.2f  %-5s %9s %9s %12s" % (
+            n, s["median_us"], s["min_us"], s.get("bound", "-"), pct(s.get("frac_nominal")),
+            pct(s.get("frac_measured")), pct(s.get("frac_measured_random_operands"))))
+    f, b = d["fwd_chain"], d["fwd_bwd_chain"]
+    L += ["", "Chains (route .. combine; route .. route_bwd + layer_load + host Partition)",
+          "  forward          median %.1f  min %.1f" % (f["median_us"], f["min_us"]),
+          "  forward+backward median %.1f  min %.1f   -> %.0f routed rows/s" % (
+              b["median_us"], b["min_us"], b["routed_rows_per_s"])]
+    if "hbm_calls_alone" in d:
+        L += ["", "HBM-bound calls alone: warm = back to back, cold = after a 1 GiB fill that evicts L2 and the "
+                  "Infinity Cache",
+              "  %-14s %12s | %8s %9s %8s %9s | %8s %9s %8s %9s" % (
+                  "call", "alg. bytes", "warm us", "GB/s", "nominal", "vs copy", "cold us", "GB/s", "nominal",
+                  "vs copy")]
+        for n, e in d["hbm_calls_alone"].items():
+            w_, c_ = e["warm"], e["cold"]
+            L.append("  %-14s %12d | %8.2f %9.1f %8s %9s | %8.2f %9.1f %8s %9s" % (
+                n, e["algorithmic_bytes"], w_["median_us"], w_["GBps"], pct(w_["frac_nominal"]),
+                pct(w_["frac_measured_copy"]), c_["median_us"], c_["GBps"], pct(c_["frac_nominal"]),
+                pct(c_["frac_measured_copy"])))
+        L.append("  ('vs copy' is against the 1 GiB copy rate; a copy of the calls' own footprint is two lines up.)")
+    if "routing_variants" in d:
+        L += ["", "Other routing histograms, same shape (forward+backward chain)"]
+        for n, e in d["routing_variants"].items():
+            L.append("  %-22s median %.1f  min %.1f  -> %.0f routed rows/s   rows per expert %s" % (
+                n, e["median_us"], e["min_us"], e["routed_rows_per_s"], e["counts"]))
+    return "\n".join(L) + "\n"
 
 
 def cpu_baseline(w, inp, sample_tokens):

@@ -207,11 +207,13 @@ int32_t dynmo_profile_read(int32_t id, double* total_ms_host, int64_t* launches_
  *
  * dynmo_peak_mfma_bf16: 256 workgroups of eight wavefronts issue `iters` x 8
  * v_mfma_f32_32x32x16_bf16 each on register operands; *flops_host (HOST) gets the
- * flop count of the launch.  sink: DEVICE, 256 * 512 floats, overwritten.
+ * flop count of the launch.  operands: DEVICE, 8 KiB of bf16 data the operand
+ * registers are filled from (random data draws the power of a real product), or
+ * NULL for fixed small numbers.  sink: DEVICE, 256 * 512 floats, overwritten.
  *
  * dynmo_peak_copy: plain streaming copy of `bytes` (a multiple of 16; DEVICE
  * pointers, 16-byte aligned, not overlapping): reads `bytes`, writes `bytes`. */
-int32_t dynmo_peak_mfma_bf16(int32_t iters, float* sink, double* flops_host, void* stream);
+int32_t dynmo_peak_mfma_bf16(int32_t iters, const void* operands, float* sink, double* flops_host, void* stream);
 int32_t dynmo_peak_copy(void* dst, const void* src, size_t bytes, void* stream);
 
 #ifdef __cplusplus

@@ -65,7 +65,7 @@ SIGNATURES = {
     "dynmo_profile_kernel_count": (_I, []),
     "dynmo_profile_kernel_name": (C.c_char_p, [_I]),
     "dynmo_profile_read": (_I, [_I, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
-    "dynmo_peak_mfma_bf16": (_I, [_I, _P, C.POINTER(C.c_double), _P]),
+    "dynmo_peak_mfma_bf16": (_I, [_I, _P, _P, C.POINTER(C.c_double), _P]),
     "dynmo_peak_copy": (_I, [_P, _P, C.c_size_t, _P]),
 }
 
@@ -257,10 +257,11 @@ def dynmo_profile_read(i):
     return ms.value, n.value
 
 
-def dynmo_peak_mfma_bf16(iters, sink, stream=None):
+def dynmo_peak_mfma_bf16(iters, sink, operands=None, stream=None):
     """Launches the register-resident MFMA loop; returns the launch's flop count."""
     fl = C.c_double()
-    _check("dynmo_peak_mfma_bf16", lib().dynmo_peak_mfma_bf16(int(iters), _ptr(sink), C.byref(fl), _stream(stream)))
+    _check("dynmo_peak_mfma_bf16", lib().dynmo_peak_mfma_bf16(int(iters), _ptr(operands), _ptr(sink), C.byref(fl),
+                                                              _stream(stream)))
     return fl.value
 
 

@@ -13,13 +13,25 @@ constexpr int kPeakBlocks = 256, kPeakThreads = 512, kPeakAcc = 8;
 
 // Eight wavefronts per workgroup (two per SIMD), eight independent accumulator
 // blocks per wavefront: every MFMA has its operands in registers and depends only
-// on the MFMA issued eight instructions earlier.
-__global__ __launch_bounds__(kPeakThreads, 1) void peak_mfma_kernel(float* __restrict__ sink, int iters) {
-  bf16x8_t a, b;
+// on the MFMA issued eight instructions earlier.  The operands are either fixed
+// small numbers (few bits change between MFMAs: the least power the loop can draw)
+// or four A and four B fragments per lane taken from the caller's buffer (random
+// data makes the loop draw what a real product draws, and the clock follows).
+__global__ __launch_bounds__(kPeakThreads, 1) void peak_mfma_kernel(const u32x4* __restrict__ operands,
+                                                                    float* __restrict__ sink, int iters) {
+  bf16x8_t a[4], b[4];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    a[j] = (__bf16)(0.001f * (threadIdx.x & 63) + j);
-    b[j] = (__bf16)(0.5f * j);
+  for (int q = 0; q < 4; ++q) {
+    if (operands) {
+      a[q] = __builtin_bit_cast(bf16x8_t, operands[q * 64 + (threadIdx.x & 63)]);
+      b[q] = __builtin_bit_cast(bf16x8_t, operands[(4 + q) * 64 + (threadIdx.x & 63)]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        a[q][j] = (__bf16)(0.001f * (threadIdx.x & 63) + j);
+        b[q][j] = (__bf16)(0.5f * j);
+      }
+    }
   }
   f32x16_t acc[kPeakAcc];
 #pragma unroll
@@ -28,7 +40,8 @@ __global__ __launch_bounds__(kPeakThreads, 1) void peak_mfma_kernel(float* __res
     for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int i = 0; i < kPeakAcc; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+    for (int i = 0; i < kPeakAcc; ++i)
+      acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i & 3], b[(i >> 1) & 3], acc[i], 0, 0, 0);
   }
   float s = 0.f;
 #pragma unroll
@@ -51,9 +64,11 @@ __global__ __launch_bounds__(256) void peak_copy_kernel(const u32x4* __restrict_
 
 using namespace dynmo;
 
-extern "C" int32_t dynmo_peak_mfma_bf16(int32_t iters, float* sink, double* flops_host, void* stream) {
+extern "C" int32_t dynmo_peak_mfma_bf16(int32_t iters, const void* operands, float* sink, double* flops_host,
+                                        void* stream) {
   if (iters <= 0 || !sink || !flops_host) return DYNMO_EINVAL;
-  peak_mfma_kernel<<<dim3(kPeakBlocks), dim3(kPeakThreads), 0, (hipStream_t)stream>>>(sink, iters);
+  peak_mfma_kernel<<<dim3(kPeakBlocks), dim3(kPeakThreads), 0, (hipStream_t)stream>>>((const u32x4*)operands, sink,
+                                                                                      iters);
   DYNMO_LAUNCH_CHECK();
   // one 32x32x16 MFMA = 2 * 32 * 32 * 16 flop per wavefront
   *flops_host = (double)kPeakBlocks * (kPeakThreads / 64) * (double)iters * kPeakAcc * 32768.0;

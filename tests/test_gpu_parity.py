@@ -465,3 +465,7 @@ def test_peak_reference_kernels():
     torch.cuda.synchronize()
     assert flops == 256 * 8 * 10 * 8 * 32768.0
     assert bool(torch.isfinite(sink).all())
+    operands = torch.randn(4096, device="cuda").to(torch.bfloat16)
+    assert B.dynmo_peak_mfma_bf16(10, sink, operands) == flops
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(sink).all())
