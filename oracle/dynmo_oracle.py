@@ -399,6 +399,68 @@ def uniform_bounds(L, S):
     return np.asarray(b, dtype=I32)
 
 
+def potential(stage_load):
+    """Sec. 3.3 (proof of Lemma 2): phi = sum over unordered worker pairs of |x_u - x_v|."""
+    x = _f64(stage_load)
+    return float(sum(abs(x[u] - x[v]) for u in range(x.size) for v in range(u + 1, x.size)))
+
+
+def diffusion_balance(loads, bounds, layer_mem=None, max_mem=float("inf"), gamma=0.0, max_rounds=10 ** 6):
+    """Diffusion balancer (Sec. 3.3: iterative, decentralised; layers move from
+    overloaded workers to underloaded neighbours; the potential phi of Lemma 2
+    never increases and the run stops once phi <= gamma).
+
+    The paper gives the idea, not a listing.  This reading is taken:
+      * workers are the pipeline stages in order and a stage's neighbours are
+        the stages next to it: a stage hands its last layer to the next stage
+        or its first layer to the previous one, so stages stay contiguous;
+      * one round = one transfer: among all single-layer transfers between
+        neighbours that keep the source non-empty, fit the receiver's memory
+        (sum of layer_mem on it + the layer <= max_mem) and strictly reduce
+        phi, the one with the largest reduction is applied (ties: the lower
+        boundary first, then the transfer towards the higher stage);
+      * the run ends when phi <= gamma, when no transfer reduces phi, or after
+        max_rounds rounds.
+    loads[l] is the load of layer l (by Param or by Time), bounds the starting
+    contiguous assignment.  Returns (bounds, history) with history[r] = phi
+    after r rounds (history[0] = phi of the start).
+    """
+    loads = _f64(loads)
+    b = [int(v) for v in bounds]
+    S = len(b) - 1
+    mem = np.zeros_like(loads) if layer_mem is None else _f64(layer_mem)
+
+    def phi_of(bb):
+        return potential(stage_loads(loads, bb))
+
+    history = [phi_of(b)]
+    for _ in range(max_rounds):
+        if history[-1] <= gamma:
+            break
+        best = None
+        for i in range(1, S):  # boundary between stage i-1 and stage i
+            for to_right in (True, False):
+                nb = list(b)
+                if to_right:  # last layer of stage i-1 goes to stage i
+                    layer, src, dst = b[i] - 1, i - 1, i
+                    nb[i] -= 1
+                else:         # first layer of stage i goes to stage i-1
+                    layer, src, dst = b[i], i, i - 1
+                    nb[i] += 1
+                if b[src + 1] - b[src] <= 1:
+                    continue
+                if float(mem[b[dst]:b[dst + 1]].sum() + mem[layer]) > max_mem:
+                    continue
+                gain = history[-1] - phi_of(nb)
+                if gain > 0 and (best is None or gain > best[0]):
+                    best = (gain, nb)
+        if best is None:
+            break
+        b = best[1]
+        history.append(phi_of(b))
+    return np.asarray(b, dtype=I32), history
+
+
 def repack_first_fit(active_workers, mem_usage, num_layers, target_num_workers, max_mem):
     """First-fit consolidation onto fewer workers (Sec. 3.4, Algorithm 2).
 

@@ -95,3 +95,75 @@ def test_repack_hand_trace():
     # first fit skips a partner that does not fit and takes the next one
     tr, act, mem, nl = orc.repack_first_fit([1, 1, 1], [5, 6, 2], [1, 1, 1], 2, 10)
     assert tr == [(0, 2, 0)] and act == [0, 1, 1] and mem[2] == 7
+
+
+def _opt(field, cast):
+    return None if field.strip() == "-" else cast(field)
+
+
+def test_diffusion_hand_traces(golden_dir):
+    for S, start, loads, lmem, mmax, final, hist in read_golden(os.path.join(golden_dir, "diffusion_hand.txt")):
+        loads = [float(v) for v in loads.split()]
+        mem = _opt(lmem, lambda f: [float(v) for v in f.split()])
+        cap = _opt(mmax, float)
+        b, h = orc.diffusion_balance(loads, [int(v) for v in start.split()], mem,
+                                     float("inf") if cap is None else cap)
+        assert list(b) == [int(v) for v in final.split()]
+        assert h == [float(v) for v in hist.split()]
+        assert len(b) == int(S) + 1
+
+
+def test_potential_closed_form():
+    """Sum of pairwise gaps = sum_i (2i - n + 1) x_(i) over the ascending order statistics."""
+    rng = np.random.default_rng(3)
+    for _ in range(20):
+        x = rng.integers(0, 1000, size=int(rng.integers(1, 9))).astype(float)
+        xs = np.sort(x)
+        n = xs.size
+        assert orc.potential(x) == float(sum((2 * i - n + 1) * xs[i] for i in range(n)))
+    assert orc.potential([5.0]) == 0.0
+    assert orc.potential([3.0, 3.0, 3.0]) == 0.0
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_diffusion_properties(seed):
+    rng = np.random.default_rng(100 + seed)
+    for _ in range(8):
+        L = int(rng.integers(2, 14))
+        S = int(rng.integers(2, min(L, 6) + 1))
+        loads = [float(v) for v in rng.integers(1, 40, size=L)]
+        cuts = sorted(rng.choice(np.arange(1, L), size=S - 1, replace=False))
+        start = [0] + [int(c) for c in cuts] + [L]
+        b, h = orc.diffusion_balance(loads, start)
+        # phi falls strictly every round and the stages stay a contiguous, non-empty cover
+        assert all(h[i + 1] < h[i] for i in range(len(h) - 1))
+        assert b[0] == 0 and b[-1] == L and all(b[i] < b[i + 1] for i in range(S))
+        x = orc.stage_loads(loads, b)
+        assert h[-1] == orc.potential(x)
+        # it never beats the exact optimum of the Partition objective, and it never ends worse than it started
+        assert x.max() >= orc.partition_dp(loads, S)
+        assert orc.potential(x) <= orc.potential(orc.stage_loads(loads, start))
+        # the end state is a local optimum: no single neighbour transfer lowers phi
+        for i in range(1, S):
+            for d in (-1, 1):
+                nb = list(b)
+                nb[i] += d
+                if nb[i] <= nb[i - 1] or nb[i] >= nb[i + 1]:
+                    continue
+                assert orc.potential(orc.stage_loads(loads, nb)) >= h[-1]
+        # stopping rules
+        b0, h0 = orc.diffusion_balance(loads, start, gamma=h[0])
+        assert list(b0) == start and h0 == [h[0]]
+        b1, h1 = orc.diffusion_balance(loads, start, max_rounds=1)
+        assert len(h1) <= 2 and h1 == h[:len(h1)]
+
+
+def test_diffusion_respects_memory():
+    loads = [9.0, 1.0, 1.0, 1.0, 1.0, 1.0]
+    mem = [1.0] * 6
+    b, _ = orc.diffusion_balance(loads, [0, 3, 6], mem, max_mem=4.0)
+    for i in range(2):
+        assert b[i + 1] - b[i] <= 4
+    free, _ = orc.diffusion_balance(loads, [0, 3, 6])
+    assert list(free) == [0, 1, 6]          # 9 | 5 without the cap
+    assert list(b) == [0, 2, 6]             # 10 | 4: stage 1 may hold four layers at most
