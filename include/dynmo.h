@@ -185,6 +185,37 @@ int32_t dynmo_stage_loads(const double* loads_host, int32_t L, const int32_t* bo
 /* Imbalance (L_max - L_min) / mean(L) of Sec. 2, Eq. 1-2. */
 int32_t dynmo_imbalance(const double* stage_loads_host, int32_t S, double* imbalance_host);
 
+/* Potential of Sec. 3.3 (proof of Lemma 2): phi = sum over unordered pairs of stages of |x_u - x_v|. */
+int32_t dynmo_potential(const double* stage_loads_host, int32_t S, double* phi_host);
+
+/* Diffusion balancer (Sec. 3.3: iterative, layers move from overloaded workers to
+ * underloaded neighbours; phi never increases; stop once phi <= gamma).  The stages are
+ * the workers, in pipeline order, and stay contiguous: a round moves one layer across
+ * one stage boundary -- of all such transfers that keep the giving stage non-empty, fit
+ * the receiving stage's memory (sum of layer_mem_host over its layers plus the layer
+ * <= max_mem; no limit when layer_mem_host is NULL) and strictly lower phi, the one that
+ * lowers it most (ties: lower boundary, then the transfer towards the later stage).  Ends
+ * when phi <= gamma, when no transfer lowers phi, or after max_rounds rounds.
+ * bounds_host [S+1]: the starting split on entry, the result on exit.  *rounds_host gets
+ * the number of transfers made, phi_host[0] / phi_host[1] the potential before / after.
+ * Host pointers only; loads must be finite and >= 0. */
+int32_t dynmo_diffusion(const double* loads_host, int32_t L, int32_t S, int32_t* bounds_host,
+                        const double* layer_mem_host, double max_mem, double gamma, int32_t max_rounds,
+                        int32_t* rounds_host, double* phi_host);
+
+/* Re-pack (Sec. 3.4, Algorithm 2): first-fit consolidation onto fewer workers.  For every
+ * pair src < dst of active workers, while more than target_num_workers are active: if
+ * mem_usage[src] + mem_usage[dst] < max_mem, src is freed (active = 0), each of its
+ * num_layers[src] layers is listed as a transfer (src, dst, layer index on src), and dst's
+ * memory and layer count grow by src's.  A freed worker neither gives nor takes again.
+ * active_host, mem_usage_host, num_layers_host [n_workers]: in and out.  transfers_host:
+ * 3 * capacity ints; *n_transfers_host gets the number of transfers.  If they do not fit,
+ * returns DYNMO_EWORKSPACE with the needed count in *n_transfers_host and every array
+ * unchanged.  Host pointers only. */
+int32_t dynmo_repack(int32_t n_workers, int32_t* active_host, double* mem_usage_host, int32_t* num_layers_host,
+                     int32_t target_num_workers, double max_mem, int32_t* transfers_host, int32_t capacity,
+                     int32_t* n_transfers_host);
+
 /* ---- profiling step ------------------------------------------------------ */
 
 /* The paper's profiling step (Sec. 3.1, Sec. 4: the iteration after a change is

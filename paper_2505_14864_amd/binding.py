@@ -60,6 +60,11 @@ SIGNATURES = {
     "dynmo_uniform_bounds": (_I, [_I, _I, C.POINTER(C.c_int32)]),
     "dynmo_stage_loads": (_I, [C.POINTER(C.c_double), _I, C.POINTER(C.c_int32), _I, C.POINTER(C.c_double)]),
     "dynmo_imbalance": (_I, [C.POINTER(C.c_double), _I, C.POINTER(C.c_double)]),
+    "dynmo_potential": (_I, [C.POINTER(C.c_double), _I, C.POINTER(C.c_double)]),
+    "dynmo_diffusion": (_I, [C.POINTER(C.c_double), _I, _I, C.POINTER(C.c_int32), C.POINTER(C.c_double), C.c_double,
+                             C.c_double, _I, C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
+    "dynmo_repack": (_I, [_I, C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_int32), _I, C.c_double,
+                          C.POINTER(C.c_int32), _I, C.POINTER(C.c_int32)]),
     "dynmo_profile_enable": (_I, [_I]),
     "dynmo_profile_reset": (_I, []),
     "dynmo_profile_kernel_count": (_I, []),
@@ -232,6 +237,35 @@ def dynmo_imbalance(stage_loads):
 
 
 # ---- profiling step ---------------------------------------------------------
+
+def dynmo_potential(stage_loads):
+    a = _darr(stage_loads)
+    out = C.c_double()
+    _check("dynmo_potential", lib().dynmo_potential(a, len(stage_loads), C.byref(out)))
+    return out.value
+
+
+def dynmo_diffusion(loads, bounds, layer_mem=None, max_mem=float("inf"), gamma=0.0, max_rounds=1 << 30):
+    """Returns (bounds, rounds, phi_before, phi_after)."""
+    la, ba = _darr(loads), _iarr(bounds)
+    ma = _darr(layer_mem) if layer_mem is not None else None
+    rounds, phi = C.c_int32(), (C.c_double * 2)()
+    _check("dynmo_diffusion", lib().dynmo_diffusion(la, len(loads), len(bounds) - 1, ba, ma, float(max_mem),
+                                                    float(gamma), int(max_rounds), C.byref(rounds), phi))
+    return list(ba), rounds.value, phi[0], phi[1]
+
+
+def dynmo_repack(active_workers, mem_usage, num_layers, target_num_workers, max_mem, capacity=None):
+    """Returns (transfers, active_workers, mem_usage, num_layers) like the listing's state after the run."""
+    n = len(active_workers)
+    act, mem, nl = _iarr(active_workers), _darr(mem_usage), _iarr(num_layers)
+    cap = n * max(1, sum(int(v) for v in num_layers)) if capacity is None else int(capacity)
+    tr = (C.c_int32 * max(1, 3 * cap))()
+    cnt = C.c_int32()
+    _check("dynmo_repack", lib().dynmo_repack(n, act, mem, nl, int(target_num_workers), float(max_mem), tr, cap,
+                                              C.byref(cnt)))
+    return [tuple(tr[3 * i:3 * i + 3]) for i in range(cnt.value)], list(act), list(mem), list(nl)
+
 
 def dynmo_profile_enable(on):
     _check("dynmo_profile_enable", lib().dynmo_profile_enable(1 if on else 0))

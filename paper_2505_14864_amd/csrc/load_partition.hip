@@ -138,3 +138,122 @@ extern "C" int32_t dynmo_imbalance(const double* stage_loads_host, int32_t S, do
   *imbalance_host = (mx - mn) / (sum / S);
   return DYNMO_OK;
 }
+
+// ---- diffusion balancer -------------------------------------------------------
+namespace {
+double potential_of(const double* x, int S) {
+  double phi = 0.0;
+  for (int u = 0; u < S; ++u)
+    for (int v = u + 1; v < S; ++v) phi += fabs(x[u] - x[v]);
+  return phi;
+}
+
+double range_sum(const double* a, int begin, int end) {
+  double acc = 0.0;
+  for (int i = begin; i < end; ++i) acc += a[i];
+  return acc;
+}
+}  // namespace
+
+extern "C" int32_t dynmo_potential(const double* stage_loads_host, int32_t S, double* phi_host) {
+  if (!stage_loads_host || !phi_host || S <= 0) return DYNMO_EINVAL;
+  *phi_host = potential_of(stage_loads_host, S);
+  return DYNMO_OK;
+}
+
+extern "C" int32_t dynmo_diffusion(const double* loads_host, int32_t L, int32_t S, int32_t* bounds_host,
+                                   const double* layer_mem_host, double max_mem, double gamma, int32_t max_rounds,
+                                   int32_t* rounds_host, double* phi_host) {
+  if (!loads_host || !bounds_host || !rounds_host || !phi_host || L < 0 || S <= 0 || max_rounds < 0)
+    return DYNMO_EINVAL;
+  if (bounds_host[0] != 0 || bounds_host[S] != L) return DYNMO_EINVAL;
+  for (int s = 0; s < S; ++s)
+    if (bounds_host[s] > bounds_host[s + 1]) return DYNMO_EINVAL;
+  for (int i = 0; i < L; ++i)
+    if (!(loads_host[i] >= 0.0) || !isfinite(loads_host[i])) return DYNMO_EINVAL;
+  std::vector<double> x(S), trial(S);
+  for (int s = 0; s < S; ++s) x[s] = range_sum(loads_host, bounds_host[s], bounds_host[s + 1]);
+  double phi = potential_of(x.data(), S);
+  phi_host[0] = phi;
+  int rounds = 0;
+  while (rounds < max_rounds && !(phi <= gamma)) {
+    // every single-layer transfer across a stage boundary; keep the one that lowers phi most
+    double best_gain = 0.0, best_phi = phi;
+    int best_boundary = -1, best_step = 0;
+    for (int i = 1; i < S; ++i) {
+      for (int dir = 0; dir < 2; ++dir) {
+        const bool to_right = dir == 0;  // last layer of stage i-1 goes to stage i, else the reverse
+        const int src = to_right ? i - 1 : i, dst = to_right ? i : i - 1;
+        const int layer = to_right ? bounds_host[i] - 1 : bounds_host[i];
+        if (bounds_host[src + 1] - bounds_host[src] <= 1) continue;
+        if (layer_mem_host &&
+            range_sum(layer_mem_host, bounds_host[dst], bounds_host[dst + 1]) + layer_mem_host[layer] > max_mem)
+          continue;
+        // stage sums of the trial assignment, each summed over its layers in order
+        trial = x;
+        const int nb = bounds_host[i] + (to_right ? -1 : 1);
+        trial[i - 1] = range_sum(loads_host, bounds_host[i - 1], nb);
+        trial[i] = range_sum(loads_host, nb, bounds_host[i + 1]);
+        const double t_phi = potential_of(trial.data(), S);
+        const double gain = phi - t_phi;
+        if (gain > 0.0 && (best_boundary < 0 || gain > best_gain)) {
+          best_gain = gain;
+          best_phi = t_phi;
+          best_boundary = i;
+          best_step = to_right ? -1 : 1;
+        }
+      }
+    }
+    if (best_boundary < 0) break;
+    bounds_host[best_boundary] += best_step;
+    x[best_boundary - 1] = range_sum(loads_host, bounds_host[best_boundary - 1], bounds_host[best_boundary]);
+    x[best_boundary] = range_sum(loads_host, bounds_host[best_boundary], bounds_host[best_boundary + 1]);
+    phi = best_phi;
+    ++rounds;
+  }
+  *rounds_host = rounds;
+  phi_host[1] = phi;
+  return DYNMO_OK;
+}
+
+// ---- re-pack ----------------------------------------------------------------------
+extern "C" int32_t dynmo_repack(int32_t n_workers, int32_t* active_host, double* mem_usage_host,
+                                int32_t* num_layers_host, int32_t target_num_workers, double max_mem,
+                                int32_t* transfers_host, int32_t capacity, int32_t* n_transfers_host) {
+  if (!active_host || !mem_usage_host || !num_layers_host || !n_transfers_host || n_workers < 0 || capacity < 0 ||
+      (capacity > 0 && !transfers_host))
+    return DYNMO_EINVAL;
+  for (int w = 0; w < n_workers; ++w)
+    if (num_layers_host[w] < 0) return DYNMO_EINVAL;
+  // Runs on copies, so that a transfer list that does not fit leaves the caller's arrays untouched.
+  std::vector<int32_t> act(active_host, active_host + n_workers), nl(num_layers_host, num_layers_host + n_workers);
+  std::vector<double> mem(mem_usage_host, mem_usage_host + n_workers);
+  std::vector<int32_t> moves;
+  int active = 0;
+  for (int w = 0; w < n_workers; ++w) active += act[w] ? 1 : 0;
+  for (int src = 0; src < n_workers; ++src) {
+    for (int dst = src + 1; dst < n_workers; ++dst) {
+      if (!act[src] || !act[dst]) continue;  // a freed worker neither gives nor takes
+      if (mem[src] + mem[dst] < max_mem && active > target_num_workers) {
+        act[src] = 0;
+        --active;
+        for (int lyr = 0; lyr < nl[src]; ++lyr) {
+          moves.push_back(src);
+          moves.push_back(dst);
+          moves.push_back(lyr);
+        }
+        mem[dst] += mem[src];
+        nl[dst] += nl[src];
+      }
+    }
+  }
+  *n_transfers_host = (int32_t)(moves.size() / 3);
+  if ((int64_t)moves.size() / 3 > capacity) return DYNMO_EWORKSPACE;
+  for (size_t i = 0; i < moves.size(); ++i) transfers_host[i] = moves[i];
+  for (int w = 0; w < n_workers; ++w) {
+    active_host[w] = act[w];
+    mem_usage_host[w] = mem[w];
+    num_layers_host[w] = nl[w];
+  }
+  return DYNMO_OK;
+}

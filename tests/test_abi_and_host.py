@@ -95,3 +95,64 @@ def test_partition_matches_oracle_dp(seed):
         if sum(st) > 0:
             assert B.dynmo_imbalance(st) == pytest.approx(orc.imbalance(st), rel=1e-14)
         assert B.dynmo_uniform_bounds(L, S) == list(orc.uniform_bounds(L, S))
+
+
+def test_diffusion_golden(golden_dir):
+    for S, start, loads, lmem, mmax, final, hist in read_golden(os.path.join(golden_dir, "diffusion_hand.txt")):
+        loads = [float(v) for v in loads.split()]
+        mem = None if lmem == "-" else [float(v) for v in lmem.split()]
+        cap = float("inf") if mmax == "-" else float(mmax)
+        h = [float(v) for v in hist.split()]
+        b, rounds, phi0, phi1 = B.dynmo_diffusion(loads, [int(v) for v in start.split()], mem, cap)
+        assert b == [int(v) for v in final.split()]
+        assert (rounds, phi0, phi1) == (len(h) - 1, h[0], h[-1])
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_diffusion_matches_oracle(seed):
+    """Same transfers as the oracle on integer-valued loads (every sum is exact, so both
+    sides see the same gains and ties); on fractional loads the invariants."""
+    rng = np.random.default_rng(300 + seed)
+    for _ in range(20):
+        L = int(rng.integers(2, 30))
+        S = int(rng.integers(2, min(L, 8) + 1))
+        cuts = sorted(rng.choice(np.arange(1, L), size=S - 1, replace=False))
+        start = [0] + [int(c) for c in cuts] + [L]
+        exact = seed % 2 == 0
+        loads = [float(v) for v in (rng.integers(0, 60, size=L) if exact else rng.random(L) * 10.0)]
+        mem, cap = None, float("inf")
+        if seed % 3 == 0:
+            mem = [float(v) for v in rng.integers(1, 4, size=L)]
+            cap = float(max(sum(mem[start[i]:start[i + 1]]) for i in range(S)) + 2)
+        gamma = float(rng.choice([0.0, 5.0, 50.0]))
+        limit = int(rng.choice([1, 3, 1000]))
+        b, rounds, phi0, phi1 = B.dynmo_diffusion(loads, start, mem, cap, gamma, limit)
+        assert b[0] == 0 and b[-1] == L and all(b[i] < b[i + 1] for i in range(S))
+        assert B.dynmo_potential(orc.stage_loads(loads, start)) == pytest.approx(phi0, rel=1e-13)
+        assert orc.potential(orc.stage_loads(loads, b)) == pytest.approx(phi1, rel=1e-12, abs=1e-12)
+        assert phi1 <= phi0 and rounds <= limit
+        if mem is not None:
+            assert all(sum(mem[b[i]:b[i + 1]]) <= cap for i in range(S))
+        if exact:
+            rb, rh = orc.diffusion_balance(loads, start, mem, cap, gamma, limit)
+            assert b == list(rb) and rounds == len(rh) - 1 and phi0 == rh[0] and phi1 == rh[-1]
+
+
+def test_repack_matches_oracle():
+    cases = [([1, 1, 1, 1], [3, 4, 2, 6], [2, 3, 1, 2], 2, 10), ([1, 1, 1], [6, 6, 6], [1, 1, 1], 1, 10),
+             ([1, 1], [1, 1], [4, 4], 2, 10), ([1, 1, 1], [5, 6, 2], [1, 1, 1], 2, 10), ([], [], [], 0, 1.0)]
+    rng = np.random.default_rng(7)
+    for _ in range(40):
+        n = int(rng.integers(1, 9))
+        cases.append(([int(v) for v in rng.integers(0, 2, size=n)], [float(v) for v in rng.integers(0, 12, size=n)],
+                      [int(v) for v in rng.integers(0, 5, size=n)], int(rng.integers(0, n + 1)),
+                      float(rng.integers(4, 30))))
+    for act, mem, nl, target, cap in cases:
+        got = B.dynmo_repack(act, mem, nl, target, cap)
+        ref = orc.repack_first_fit(act, mem, nl, target, cap)
+        assert got[0] == [tuple(t) for t in ref[0]]
+        assert got[1] == ref[1] and got[2] == ref[2] and got[3] == ref[3]
+    # a transfer list that does not fit is reported, with nothing changed
+    with pytest.raises(B.DynmoError) as e:
+        B.dynmo_repack([1, 1, 1, 1], [3, 4, 2, 6], [2, 3, 1, 2], 2, 10, capacity=1)
+    assert e.value.status == -3
