@@ -30,6 +30,10 @@ def parse():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run one plain 1 GiB device copy (a known-size reference for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--reroute", type=int, default=0, metavar="N",
+                    help="instead of the headline line: N iterations with fresh router inputs each (the routing "
+                         "decision changes every iteration), the exported loads rebalanced every iteration; prints "
+                         "the imbalance before/after per iteration and the balancers' host time")
     ap.add_argument("--protocol-text", default="", help="with --protocol: also write the result as a text table here")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="tokens in the oracle's timed sample (0 = auto)")
     ap.add_argument("--protocol", action="store_true",
@@ -126,6 +130,9 @@ def main():
             B.dynmo_partition(per_task, stage_split)
         return rows, per_task
 
+    if a.reroute > 0:
+        print(json.dumps(reroute(a, w, dev, layers, step, stage_split)))
+        return
     if a.protocol:
         res = protocol(a, w, inp, dev, layers, Ws, step)
         if a.protocol_text:
@@ -233,6 +240,62 @@ def main():
         "input_generation_s": round(gen_s, 1),
     }
     print(json.dumps(out))
+
+
+def reroute(a, w, dev, layers, step, S):
+    """Sec. 3.3 / Sec. 4: for MoE and MoD the load changes with every routing decision, so
+    the balancer runs every iteration.  Each iteration draws new router inputs on the
+    device, runs the whole path, exports the loads and rebalances them on the host with
+    both balancers; reports the imbalance of the static equal split, of Partition and of
+    Diffusion (started from the previous iteration's split), and what the balancing costs."""
+    import torch
+    from paper_2505_14864_amd import binding as B
+    from paper_2505_14864_amd import workloads as wl
+
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(w.seed)
+    bias = torch.from_numpy(wl.expert_bias(w)).cuda() if w.mode == "moe" else None
+    for _ in range(max(1, a.warmup)):
+        step()
+    torch.cuda.synchronize()
+    rec = {"uniform": [], "partition": [], "diffusion": [], "diffusion_rounds": []}
+    t_step, t_bal = [], []
+    prev = None
+    for it in range(a.reroute):
+        # the routing decision of this iteration (drifting preference: the bias rotates over the experts)
+        if w.mode == "moe":
+            dev["logits"] = torch.randn(w.T, w.E, generator=gen, device="cuda") + torch.roll(bias, it)[None, :]
+        elif w.mode == "mod":
+            dev["scores"] = torch.randn(w.B, w.S, generator=gen, device="cuda")
+        else:
+            dev["exit_layer"] = torch.empty(w.T, device="cuda").geometric_(w.exit_p, generator=gen).to(torch.int32)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        _, loads = step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        if len(loads) < S or sum(loads) <= 0:
+            continue
+        ub = B.dynmo_uniform_bounds(len(loads), S)
+        pb, _ = B.dynmo_partition(loads, S)
+        db, rounds, _, _ = B.dynmo_diffusion(loads, prev if prev is not None else ub)
+        t2 = time.perf_counter()
+        prev = db
+        rec["uniform"].append(round(B.dynmo_imbalance(B.dynmo_stage_loads(loads, ub)), 4))
+        rec["partition"].append(round(B.dynmo_imbalance(B.dynmo_stage_loads(loads, pb)), 4))
+        rec["diffusion"].append(round(B.dynmo_imbalance(B.dynmo_stage_loads(loads, db)), 4))
+        rec["diffusion_rounds"].append(rounds)
+        t_step.append(t1 - t0)
+        t_bal.append(t2 - t1)
+    n = max(1, len(t_step))
+    mean = lambda xs: sum(xs) / max(1, len(xs))
+    return {"workload": "config %d: %s" % (a.config, w.name), "iterations": a.reroute, "stages": S,
+            "tasks": "layers" if len(layers) > 1 else "experts",
+            "imbalance": rec,
+            "mean_imbalance": {k: round(mean(v), 4) for k, v in rec.items() if k != "diffusion_rounds"},
+            "ms_per_iteration": round(1e3 * sum(t_step) / n, 4),
+            "balancing_us_per_iteration": round(1e6 * sum(t_bal) / n, 1),
+            "balancing_overhead": round(sum(t_bal) / max(1e-12, sum(t_step)), 5)}
 
 
 def _stats(xs):
