@@ -104,6 +104,7 @@ size_t dynmo_permute_workspace_bytes(const dynmo_desc* d);
  * keyed by expert: row p = seg_offsets[e] + (number of earlier slots of expert e).
  * x [T,H], expert_idx [T,k] -> x_p [T*k,H] (x_p[p] = x[src_slot[p] / k]),
  * seg_offsets [E+1], src_slot [T*k], dst_pos [T,k] (-1 if unrouted).
+ * With x_p = NULL only the indices are produced (x may then be NULL too).
  * The result is deterministic (no dependence on atomic ordering). */
 int32_t dynmo_permute(const dynmo_desc* d, const void* x, const int32_t* expert_idx, void* x_p,
                       int32_t* seg_offsets, int32_t* src_slot, int32_t* dst_pos, void* workspace,
@@ -129,6 +130,17 @@ size_t dynmo_grouped_ffn_fwd_workspace_bytes(const dynmo_desc* d);
 int32_t dynmo_grouped_ffn_fwd(const dynmo_desc* d, const void* x_p, const int32_t* seg_offsets, const void* Wg,
                               const void* Wu, const void* Wd, void* y_p, void* G_save, void* U_save,
                               void* workspace, size_t workspace_bytes, void* stream);
+
+/* The same layer with the row gather fused into the first product: the rows are read
+ * straight from the token-ordered input, row p of the expert-sorted order being
+ * x[src_slot[p] / k] (R^-1(e) of Sec. 2.1 applied inside the kernel's loads), so a
+ * forward-only caller can skip the row copy of dynmo_permute (x_p = NULL there).
+ * x [T,H], src_slot [T*k] as written by dynmo_permute; everything else, and the
+ * workspace size, as for dynmo_grouped_ffn_fwd. */
+int32_t dynmo_grouped_ffn_fwd_gather(const dynmo_desc* d, const void* x, const int32_t* src_slot,
+                                     const int32_t* seg_offsets, const void* Wg, const void* Wu, const void* Wd,
+                                     void* y_p, void* G_save, void* U_save, void* workspace, size_t workspace_bytes,
+                                     void* stream);
 
 size_t dynmo_grouped_ffn_bwd_workspace_bytes(const dynmo_desc* d);
 

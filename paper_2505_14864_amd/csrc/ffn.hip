@@ -26,19 +26,37 @@ extern "C" size_t dynmo_grouped_ffn_bwd_workspace_bytes(const dynmo_desc* d) {
   return 3 * act_bytes(d) + mfma_scratch(d) + 256;  // dG, dU, A
 }
 
-extern "C" int32_t dynmo_grouped_ffn_fwd(const dynmo_desc* d, const void* x_p, const int32_t* seg_offsets,
-                                         const void* Wg, const void* Wu, const void* Wd, void* y_p, void* G_save,
-                                         void* U_save, void* workspace, size_t workspace_bytes, void* stream) {
+namespace dynmo {
+static int32_t ffn_fwd_entry(const dynmo_desc* d, const void* rows, const int32_t* gather, const int32_t* seg_offsets,
+                             const void* Wg, const void* Wu, const void* Wd, void* y_p, void* G_save, void* U_save,
+                             void* workspace, size_t workspace_bytes, void* stream) {
   int32_t rc = check_desc(d);
   if (rc) return rc;
-  if (!x_p || !seg_offsets || !Wg || !Wu || !Wd || !y_p || !G_save || !U_save || !workspace) return DYNMO_EINVAL;
+  if (!rows || !seg_offsets || !Wg || !Wu || !Wd || !y_p || !G_save || !U_save || !workspace) return DYNMO_EINVAL;
   if (workspace_bytes < dynmo_grouped_ffn_fwd_workspace_bytes(d)) return DYNMO_EWORKSPACE;
   if (max_m_tiles(d, 64) > 65535) return DYNMO_EUNSUPPORTED;
   void* A = (void*)align_up((size_t)workspace, 256);
   if (ffn_mfma_supported(d))
-    return ffn_fwd_mfma(d, x_p, seg_offsets, Wg, Wu, Wd, y_p, G_save, U_save, A, (char*)A + act_bytes(d),
+    return ffn_fwd_mfma(d, rows, gather, seg_offsets, Wg, Wu, Wd, y_p, G_save, U_save, A, (char*)A + act_bytes(d),
                         (hipStream_t)stream);
-  return ffn_fwd_generic(d, x_p, seg_offsets, Wg, Wu, Wd, y_p, G_save, U_save, A, (hipStream_t)stream);
+  return ffn_fwd_generic(d, rows, gather, seg_offsets, Wg, Wu, Wd, y_p, G_save, U_save, A, (hipStream_t)stream);
+}
+}  // namespace dynmo
+
+extern "C" int32_t dynmo_grouped_ffn_fwd(const dynmo_desc* d, const void* x_p, const int32_t* seg_offsets,
+                                         const void* Wg, const void* Wu, const void* Wd, void* y_p, void* G_save,
+                                         void* U_save, void* workspace, size_t workspace_bytes, void* stream) {
+  return ffn_fwd_entry(d, x_p, nullptr, seg_offsets, Wg, Wu, Wd, y_p, G_save, U_save, workspace, workspace_bytes,
+                       stream);
+}
+
+extern "C" int32_t dynmo_grouped_ffn_fwd_gather(const dynmo_desc* d, const void* x, const int32_t* src_slot,
+                                                const int32_t* seg_offsets, const void* Wg, const void* Wu,
+                                                const void* Wd, void* y_p, void* G_save, void* U_save,
+                                                void* workspace, size_t workspace_bytes, void* stream) {
+  if (!src_slot) return DYNMO_EINVAL;
+  return ffn_fwd_entry(d, x, src_slot, seg_offsets, Wg, Wu, Wd, y_p, G_save, U_save, workspace, workspace_bytes,
+                       stream);
 }
 
 extern "C" int32_t dynmo_grouped_ffn_bwd(const dynmo_desc* d, const void* dy_p, const void* x_p, const void* G_save,

@@ -12,11 +12,14 @@ namespace dynmo {
 constexpr int GT = 64;  // tile rows and columns
 constexpr int GK = 16;  // k step
 
-// S[kk][r] = base[(row0+r)*rs + (k0+kk)*ks], zero outside [.., row_end) x [.., k_end).
-// The thread mapping follows whichever stride is 1 so that loads coalesce.
+// S[kk][r] = base[row(row0+r)*rs + (k0+kk)*ks], zero outside [.., row_end) x [.., k_end).
+// row(i) = i, or rowmap[i] / rowdiv when the rows are gathered through an index
+// (K-contiguous operands only).  The thread mapping follows whichever stride is 1
+// so that loads coalesce.
 template <typename T>
 __device__ __forceinline__ void stage_tile(float (*S)[GT + 1], const T* __restrict__ base, long rs, long ks, int row0,
-                                           int row_end, int k0, int k_end) {
+                                           int row_end, int k0, int k_end, const int32_t* __restrict__ rowmap = nullptr,
+                                           int rowdiv = 1) {
   const int tid = threadIdx.x;
   if (ks == 1) {
     const int kk = tid % GK;
@@ -24,7 +27,10 @@ __device__ __forceinline__ void stage_tile(float (*S)[GT + 1], const T* __restri
     for (int j = 0; j < GT / (256 / GK); ++j) {
       const int r = tid / GK + j * (256 / GK);
       float v = 0.f;
-      if (row0 + r < row_end && k0 + kk < k_end) v = Elem<T>::load(base + (long)(row0 + r) * rs + (long)(k0 + kk));
+      if (row0 + r < row_end && k0 + kk < k_end) {
+        const long row = rowmap ? rowmap[row0 + r] / rowdiv : row0 + r;
+        v = Elem<T>::load(base + row * rs + (long)(k0 + kk));
+      }
       S[kk][r] = v;
     }
   } else {
@@ -43,10 +49,11 @@ __device__ __forceinline__ void stage_tile(float (*S)[GT + 1], const T* __restri
 template <typename T>
 __device__ __forceinline__ void mac_phase(float (&acc)[4][4], const T* A, long a_rs, long a_ks, int m0, int m_end,
                                           const T* B, long b_rs, long b_ks, int n0, int n_end, int k_begin, int k_end,
-                                          float (*As)[GT + 1], float (*Bs)[GT + 1]) {
+                                          float (*As)[GT + 1], float (*Bs)[GT + 1],
+                                          const int32_t* __restrict__ a_rowmap = nullptr, int a_rowdiv = 1) {
   const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
   for (int k0 = k_begin; k0 < k_end; k0 += GK) {
-    stage_tile<T>(As, A, a_rs, a_ks, m0, m_end, k0, k_end);
+    stage_tile<T>(As, A, a_rs, a_ks, m0, m_end, k0, k_end, a_rowmap, a_rowdiv);
     stage_tile<T>(Bs, B, b_rs, b_ks, n0, n_end, k0, k_end);
     __syncthreads();
 #pragma unroll
@@ -66,18 +73,21 @@ __device__ __forceinline__ void mac_phase(float (&acc)[4][4], const T* A, long a
 }
 
 // G = X Wg^T, U = X Wu^T, A = silu(G) U for one 64x64 tile of one expert segment.
+// With `gather`, row p of X is x_p[gather[p] / gather_div] (rows fetched from the
+// token-ordered input through the slot index).
 template <typename T>
 __global__ __launch_bounds__(256) void gateup_generic_kernel(const T* __restrict__ x_p, const int32_t* __restrict__ seg,
                                                              const T* __restrict__ Wg, const T* __restrict__ Wu,
                                                              T* __restrict__ G, T* __restrict__ U, T* __restrict__ A, int E,
-                                                             int H, int F) {
+                                                             int H, int F, const int32_t* __restrict__ gather,
+                                                             int gather_div) {
   __shared__ float As[GK][GT + 1], Bs[GK][GT + 1];
   int e, m0, m_end;
   if (!find_m_tile(seg, E, blockIdx.y, GT, &e, &m0, &m_end)) return;
   const int n0 = blockIdx.x * GT;
   float accG[4][4] = {}, accU[4][4] = {};
-  mac_phase<T>(accG, x_p, H, 1, m0, m_end, Wg + (long)e * F * H, H, 1, n0, F, 0, H, As, Bs);
-  mac_phase<T>(accU, x_p, H, 1, m0, m_end, Wu + (long)e * F * H, H, 1, n0, F, 0, H, As, Bs);
+  mac_phase<T>(accG, x_p, H, 1, m0, m_end, Wg + (long)e * F * H, H, 1, n0, F, 0, H, As, Bs, gather, gather_div);
+  mac_phase<T>(accU, x_p, H, 1, m0, m_end, Wu + (long)e * F * H, H, 1, n0, F, 0, H, As, Bs, gather, gather_div);
   const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -163,13 +173,14 @@ __global__ __launch_bounds__(256) void dw_generic_kernel(const int32_t* __restri
 }
 
 template <typename T>
-static int32_t fwd_generic_t(const dynmo_desc* d, const void* x_p, const int32_t* seg, const void* Wg, const void* Wu,
-                             const void* Wd, void* y_p, void* G, void* U, void* A, hipStream_t st) {
+static int32_t fwd_generic_t(const dynmo_desc* d, const void* x_p, const int32_t* gather, const int32_t* seg,
+                             const void* Wg, const void* Wu, const void* Wd, void* y_p, void* G, void* U, void* A,
+                             hipStream_t st) {
   const int m_tiles = max_m_tiles(d, GT);
   if (m_tiles == 0) return DYNMO_OK;
   const long FH = (long)d->F * d->H;
   DYNMO_TIMED_LAUNCH(K_FFN_GATEUP, st, gateup_generic_kernel<T><<<dim3((d->F + GT - 1) / GT, m_tiles), dim3(256), 0, st>>>(
-      (const T*)x_p, seg, (const T*)Wg, (const T*)Wu, (T*)G, (T*)U, (T*)A, d->E, d->H, d->F));
+      (const T*)x_p, seg, (const T*)Wg, (const T*)Wu, (T*)G, (T*)U, (T*)A, d->E, d->H, d->F, gather, d->k));
   // Y = A Wd^T : B(n=h, k=f) = Wd[e][h*F + f]
   DYNMO_TIMED_LAUNCH(K_FFN_DOWN, st, seg_gemm_generic_kernel<T, EPI_STORE><<<dim3((d->H + GT - 1) / GT, m_tiles), dim3(256), 0, st>>>(
       seg, d->E, d->H, d->F, (const T*)A, (const T*)Wd, nullptr, nullptr, d->F, FH, d->F, 1, (T*)y_p, nullptr, nullptr,
@@ -201,10 +212,10 @@ static int32_t bwd_generic_t(const dynmo_desc* d, const void* dy_p, const void* 
   return DYNMO_OK;
 }
 
-int32_t ffn_fwd_generic(const dynmo_desc* d, const void* x_p, const int32_t* seg, const void* Wg, const void* Wu,
-                        const void* Wd, void* y_p, void* G, void* U, void* A, hipStream_t st) {
-  return d->dtype == DYNMO_BF16 ? fwd_generic_t<bf16_t>(d, x_p, seg, Wg, Wu, Wd, y_p, G, U, A, st)
-                                : fwd_generic_t<float>(d, x_p, seg, Wg, Wu, Wd, y_p, G, U, A, st);
+int32_t ffn_fwd_generic(const dynmo_desc* d, const void* x_p, const int32_t* gather, const int32_t* seg, const void* Wg,
+                        const void* Wu, const void* Wd, void* y_p, void* G, void* U, void* A, hipStream_t st) {
+  return d->dtype == DYNMO_BF16 ? fwd_generic_t<bf16_t>(d, x_p, gather, seg, Wg, Wu, Wd, y_p, G, U, A, st)
+                                : fwd_generic_t<float>(d, x_p, gather, seg, Wg, Wu, Wd, y_p, G, U, A, st);
 }
 
 int32_t ffn_bwd_generic(const dynmo_desc* d, const void* dy_p, const void* x_p, const void* G, const void* U,

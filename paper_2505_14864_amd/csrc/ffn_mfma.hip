@@ -79,6 +79,8 @@ struct GemmParams {
   const bf16_t* G;
   const bf16_t* U;
   float* partial;     // kMaxPersistent fp32 partial tiles, then kSplitHdrInts ints (modes that may split k)
+  const int32_t* gather;  // MODE_GATEUP: row p of operand A is row gather[p] / gather_div of A1, or nullptr
+  int gather_div;
 };
 
 // ---- global -> registers -> LDS staging ---------------------------------------
@@ -145,6 +147,24 @@ __device__ __forceinline__ void store_piece(char* tile, const u32x4& v, int j) {
     *(u32x4*)(tile + (c >> 3) * kPitchK + (c & 7) * 16) = v;
   else
     *(u32x4*)(tile + (c >> 5) * kPitchT + (c & 31) * 16) = v;
+}
+
+// [row][k] memory whose rows are fetched through an index: piece j is row
+// rowmap[row0 + tid/8 + 64 j] / rowdiv of the operand, so the offsets are taken from the
+// operand's first row (the buffer base then points at (row 0, k0)).
+__device__ __forceinline__ Pieces pieces_rowk_gather(uint32_t ld_bytes, int row0, int rows_left,
+                                                     const int32_t* __restrict__ rowmap, int rowdiv) {
+  Pieces ps;
+  const int tid = threadIdx.x;
+  const int r0 = tid >> 3, kc = (tid & 7) * 8;
+#pragma unroll
+  for (int j = 0; j < kPieces; ++j) {
+    const int row = r0 + (kMfmaThreads / 8) * j;
+    ps.off[j] = kOob;
+    if (row < rows_left) ps.off[j] = (uint32_t)(rowmap[row0 + row] / rowdiv) * ld_bytes + kc * 2;
+    ps.kpos[j] = kc;
+  }
+  return ps;
 }
 
 // ---- LDS -> MFMA operand fragments ---------------------------------------------
@@ -376,7 +396,10 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   u32x4 ra[kPieces], rb[kPieces];
   bf16x8_t fa[2][2], fb[2][4];
   const uint32_t lda_b = (uint32_t)p.lda * 2, ldb_b = (uint32_t)p.ldb * 2;
-  const Pieces pa = A_TRANS ? pieces_krow(lda_b, t.m_end - t.m0) : pieces_rowk(lda_b, t.m_end - t.m0, 256);
+  const bool gathered = MODE == MODE_GATEUP && p.gather != nullptr;
+  const Pieces pa = A_TRANS   ? pieces_krow(lda_b, t.m_end - t.m0)
+                    : gathered ? pieces_rowk_gather(lda_b, t.m0, t.m_end - t.m0, p.gather, p.gather_div)
+                               : pieces_rowk(lda_b, t.m_end - t.m0, 256);
   const Pieces pb = B_TRANS ? pieces_krow(ldb_b, n_end - t.n0)
                             : pieces_rowk(ldb_b, n_end - t.n0, MODE == MODE_GATEUP ? 128 : 256);
 
@@ -393,7 +416,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     q.k_left = kt < kt_hi ? k_end - k0 : 0;
     const bf16_t* A = ph == 0 ? p.A1 : p.A2;
     const bf16_t* B = (MODE == MODE_DX && ph == 1) ? B2 : B1;
-    q.a = make_rsrc(A_TRANS ? A + (long)k0 * p.lda + t.m0 : A + (long)t.m0 * p.lda + k0);
+    q.a = make_rsrc(A_TRANS ? A + (long)k0 * p.lda + t.m0 : A + (gathered ? 0 : (long)t.m0 * p.lda) + k0);
     q.b_lo = make_rsrc(B_TRANS ? B + (long)k0 * p.ldb + t.n0 : B + (long)t.n0 * p.ldb + k0);
     q.b_hi = MODE == MODE_GATEUP ? make_rsrc(B2 + (long)t.n0 * p.ldb + k0) : q.b_lo;
     return q;
@@ -667,12 +690,16 @@ static int32_t launch_mfma(const GemmParams& p, int max_tiles, KernelId id, hipS
 }
 
 bool ffn_mfma_supported(const dynmo_desc* d) {
+  // piece offsets are 32-bit with the top bit as the "outside" marker: a whole operand's
+  // rows (the gathered input) and a tile's rows must stay below 2 GiB
   return d->dtype == DYNMO_BF16 && d->H % 8 == 0 && d->F % 8 == 0 &&
-         (int64_t)max_m_tiles(d, BM) * ((d->F + 127) / 128) < (1 << 30);
+         (int64_t)max_m_tiles(d, BM) * ((d->F + 127) / 128) < (1 << 30) &&
+         (int64_t)d->T * d->H * 2 < ((int64_t)1 << 31);
 }
 
-int32_t ffn_fwd_mfma(const dynmo_desc* d, const void* x_p, const int32_t* seg, const void* Wg, const void* Wu,
-                     const void* Wd, void* y_p, void* G, void* U, void* A, void* scratch, hipStream_t st) {
+int32_t ffn_fwd_mfma(const dynmo_desc* d, const void* x_p, const int32_t* gather, const int32_t* seg, const void* Wg,
+                     const void* Wu, const void* Wd, void* y_p, void* G, void* U, void* A, void* scratch,
+                     hipStream_t st) {
   const int mt = max_m_tiles(d, BM);
   const long FH = (long)d->F * d->H;
   GemmParams p = {};
@@ -682,6 +709,8 @@ int32_t ffn_fwd_mfma(const dynmo_desc* d, const void* x_p, const int32_t* seg, c
   p.N = d->F;
   p.K = d->H;
   p.A1 = (const bf16_t*)x_p;
+  p.gather = gather;
+  p.gather_div = d->k;
   p.lda = d->H;
   p.B1 = (const bf16_t*)Wg;
   p.B2 = (const bf16_t*)Wu;

@@ -259,7 +259,7 @@ extern "C" int32_t dynmo_permute(const dynmo_desc* d, const void* x, const int32
                                  size_t workspace_bytes, void* stream) {
   int32_t rc = check_desc(d);
   if (rc) return rc;
-  if (!x || !expert_idx || !x_p || !seg_offsets || !src_slot || !dst_pos || !workspace) return DYNMO_EINVAL;
+  if (!expert_idx || !seg_offsets || !src_slot || !dst_pos || !workspace || (x_p && !x)) return DYNMO_EINVAL;
   if (workspace_bytes < dynmo_permute_workspace_bytes(d)) return DYNMO_EWORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   const int n_slots = d->T * d->k;
@@ -276,6 +276,7 @@ extern "C" int32_t dynmo_permute(const dynmo_desc* d, const void* x, const int32
   DYNMO_TIMED_LAUNCH(K_PERMUTE_SCATTER, st,
                      permute_scatter_kernel<<<dim3(nc), dim3(kChunkThreads), 0, st>>>(expert_idx, n_slots, d->E,
                                                                                       chunk_counts, src_slot, dst_pos));
+  if (!x_p) return DYNMO_OK;  // indices only: the caller gathers the rows itself
   if (d->k <= 2) return launch_rows<2>(d, x, dst_pos, x_p, st);
   if (d->k <= 8) return launch_rows<8>(d, x, dst_pos, x_p, st);
   return launch_rows<kMaxExperts>(d, x, dst_pos, x_p, st);

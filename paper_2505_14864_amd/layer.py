@@ -98,6 +98,17 @@ class RoutedFFNLayer:
         B.dynmo_combine(d, self.y_p, self.dst_pos, self.gate_w, x if self.residual else None, out)
         return out
 
+    def forward_gather(self, x, Wg, Wu, Wd, out=None):
+        """Forward without the row copy: the first product reads its rows from x through
+        src_slot (x_p is not written, so backward() cannot follow this call)."""
+        d = self.d
+        out = self.out if out is None else out
+        B.dynmo_permute(d, None, self.expert_idx, None, self.seg_offsets, self.src_slot, self.dst_pos, self.ws_permute)
+        B.dynmo_grouped_ffn_fwd_gather(d, x, self.src_slot, self.seg_offsets, Wg, Wu, Wd, self.y_p, self.G, self.U,
+                                       self.ws_fwd)
+        B.dynmo_combine(d, self.y_p, self.dst_pos, self.gate_w, x if self.residual else None, out)
+        return out
+
     def backward(self, dout, Wg, Wu, Wd, dx=None):
         self.alloc_backward()
         d = self.d

@@ -469,3 +469,46 @@ def test_peak_reference_kernels():
     assert B.dynmo_peak_mfma_bf16(10, sink, operands) == flops
     torch.cuda.synchronize()
     assert bool(torch.isfinite(sink).all())
+
+
+GATHER_CASES = [
+    ("moe", wl.CONFIGS[1]),                                                       # fp32, the generic kernels
+    ("moe", wl.scaled(wl.CONFIGS[2], T=700, H=256, F=448, seed=61)),              # bf16 MFMA, several tiles + tail
+    ("moe", wl.scaled(wl.CONFIGS[3], T=640, H=128, F=88, seed=62)),               # k = 4: four slots share a token row
+    ("mod", wl.scaled(wl.CONFIGS[4], T=4 * 256, B=4, S=256, cap=32, H=128, F=256, seed=63)),  # most tokens unrouted
+]
+
+
+@pytest.mark.parametrize("mode,w", GATHER_CASES, ids=lambda v: v if isinstance(v, str) else "%s-T%d" % (v.dtype, v.T))
+def test_forward_with_fused_gather(mode, w):
+    """The forward pass that reads its rows through src_slot: bit-identical to the
+    forward pass over the copied rows (same arithmetic, other addresses), and so within
+    tolerance of the oracle; x_p is never written."""
+    say("fused gather %s %s T=%d" % (mode, w.dtype, w.T))
+    inp = wl.make_inputs(w, threads=1)
+    dev = {n: to_device(a) for n, a in inp.items()}
+    a = RoutedFFNLayer(w.T, w.H, w.F, w.E, w.k, w.dtype, mode)
+    b = RoutedFFNLayer(w.T, w.H, w.F, w.E, w.k, w.dtype, mode)
+    for layer in (a, b):
+        if mode == "moe":
+            layer.route_topk(dev["logits"])
+        else:
+            layer.route_capacity(dev["scores"], w.cap)
+    b.x_p.fill_(7.0)
+    a.forward(dev["x"], dev["Wg"], dev["Wu"], dev["Wd"])
+    b.forward_gather(dev["x"], dev["Wg"], dev["Wu"], dev["Wd"])
+    torch.cuda.synchronize()
+    R = int(to_host(a.seg_offsets)[-1])
+    for n in ("seg_offsets", "src_slot", "dst_pos"):
+        assert torch.equal(getattr(a, n)[:R] if n == "src_slot" else getattr(a, n),
+                           getattr(b, n)[:R] if n == "src_slot" else getattr(b, n)), n
+    for n in ("G", "U", "y_p"):
+        assert torch.equal(getattr(a, n)[:R], getattr(b, n)[:R]), n
+    assert torch.equal(a.out, b.out)
+    assert bool((b.x_p == 7.0).all())
+    f = f32_inputs(inp)
+    if mode == "moe":
+        ref = orc.moe_layer(f["logits"], f["x"], f["Wg"], f["Wu"], f["Wd"], w.k, f["dout"])
+    else:
+        ref = orc.mod_layer(f["scores"], w.cap, f["x"], f["Wg"], f["Wu"], f["Wd"], f["dout"])
+    assert_close("out", to_host(b.out), ref["out"], TOL[w.dtype])
