@@ -71,6 +71,87 @@ def route_topk(logits, k):
     return idx.astype(I32), gate
 
 
+def route_topk_biased(logits, k, bias=None, norm="selected"):
+    """Token-choice top-k with the two variants the paper's survey of MoE routing
+    names (Sec. 2.1: bias terms added to the token-to-expert affinity scores, as
+    in auxiliary-loss-free balancing; Sec. 6: the GShard / Switch family).
+
+    Selection orders the experts by (logit + bias) -- that sum is taken in
+    float32, the precision the scores arrive in, because it decides an integer
+    -- descending, index ascending on ties.  The bias steers the selection only:
+    gate weights come from the raw logits, either as the softmax over the k
+    selected ones (norm="selected", the same as route_topk) or as the softmax
+    over all E experts read at the selected ones (norm="all").
+
+    Returns expert_idx int32 [T, k], gate_w f64 [T, k].
+    """
+    lg32 = np.asarray(logits, dtype=np.float32)
+    T, E = lg32.shape
+    if not (1 <= k <= E):
+        raise ValueError("k must be in [1, E]")
+    score = lg32 if bias is None else (lg32 + np.asarray(bias, dtype=np.float32)[None, :]).astype(np.float32)
+    order = np.argsort(-score.astype(F64), axis=1, kind="stable")
+    idx = order[:, :k]
+    lg = lg32.astype(F64)
+    sel = np.take_along_axis(lg, idx, axis=1)
+    if norm == "selected":
+        ex = np.exp(sel - sel.max(axis=1, keepdims=True))
+        gate = ex / ex.sum(axis=1, keepdims=True)
+    elif norm == "all":
+        m = lg.max(axis=1, keepdims=True)
+        gate = np.exp(sel - m) / np.exp(lg - m).sum(axis=1, keepdims=True)
+    else:
+        raise ValueError(norm)
+    return idx.astype(I32), gate
+
+
+def route_topk_biased_bwd(dgate, logits, expert_idx, norm="selected"):
+    """Gradient of the gate weights of route_topk_biased with respect to the raw
+    logits (selection and bias carry none).  With p the softmax the weights are
+    read from (over the selected logits, or over all E):
+    dlogit[e] = sum_s dgate_s * w_s * ([e == e_s] - p[e])."""
+    dg = _f64(dgate)
+    lg = _f64(logits)
+    ei = np.asarray(expert_idx).astype(np.int64)
+    T, E = lg.shape
+    out = np.zeros((T, E), F64)
+    for t in range(T):
+        if norm == "selected":
+            z = lg[t, ei[t]]
+            p_sel = np.exp(z - z.max())
+            p_sel /= p_sel.sum()
+            p = np.zeros(E, F64)
+            p[ei[t]] = p_sel
+        else:
+            p = np.exp(lg[t] - lg[t].max())
+            p /= p.sum()
+        w = p[ei[t]]
+        inner = float((dg[t] * w).sum())
+        out[t] = -p * inner
+        for s in range(ei.shape[1]):
+            out[t, ei[t, s]] += dg[t, s] * w[s]
+    return out
+
+
+def capacity_drop(expert_idx, E, capacity):
+    """Expert capacity with token dropping (Sec. 6: an expert processes at most
+    `capacity` tokens).  Slots are served in ascending flat order i = t*k + s:
+    a slot whose expert already holds `capacity` slots is dropped (-1), it is
+    not re-routed.  Returns the kept assignment, same shape."""
+    ei = np.asarray(expert_idx)
+    flat = ei.reshape(-1).astype(np.int64)
+    kept = flat.copy()
+    held = [0] * E
+    for i, e in enumerate(flat):
+        if e < 0:
+            continue
+        if held[e] >= capacity:
+            kept[i] = -1
+        else:
+            held[e] += 1
+    return kept.reshape(ei.shape).astype(I32)
+
+
 def route_capacity(scores, cap):
     """Mixture-of-Depths capacity routing (Sec. 2.6: tokens bypass a layer
     unless they are among the top-k of their sequence).

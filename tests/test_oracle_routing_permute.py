@@ -162,3 +162,100 @@ def test_counts_and_loads():
         assert t_l == int((ex >= l).sum())
         assert prev is None or t_l <= prev
         prev = t_l
+
+
+# ---- routing variants: biased selection, softmax over all experts, expert capacity ----
+
+def _brute_topk(score_row, k):
+    """k rounds of arg-max with the lower index winning ties."""
+    live = list(range(len(score_row)))
+    out = []
+    for _ in range(k):
+        best = live[0]
+        for e in live[1:]:
+            if score_row[e] > score_row[best]:
+                best = e
+        out.append(best)
+        live.remove(best)
+    return out
+
+
+def test_route_topk_biased_reduces_to_plain():
+    rng = np.random.default_rng(40)
+    lg = rng.standard_normal((200, 8)).astype(np.float32)
+    i0, w0 = orc.route_topk(lg, 2)
+    i1, w1 = orc.route_topk_biased(lg, 2)
+    assert np.array_equal(i0, i1) and np.allclose(w0, w1, rtol=1e-15, atol=0)
+    i2, w2 = orc.route_topk_biased(lg, 2, bias=np.zeros(8, np.float32), norm="selected")
+    assert np.array_equal(i0, i2) and np.array_equal(w1, w2)
+
+
+def test_route_topk_biased_selection_and_weights():
+    from scipy.special import softmax
+    rng = np.random.default_rng(41)
+    T, E, k = 300, 6, 3
+    lg = rng.standard_normal((T, E)).astype(np.float32)
+    lg[::7, 2] = lg[::7, 4]  # ties
+    bias = np.array([0.5, -0.25, 0.0, 1.0, 0.0, -2.0], np.float32)
+    idx, w = orc.route_topk_biased(lg, k, bias, norm="all")
+    score = (lg + bias[None, :]).astype(np.float32)
+    p = softmax(lg.astype(np.float64), axis=1)
+    for t in range(T):
+        assert list(idx[t]) == _brute_topk(score[t], k)
+        assert np.allclose(w[t], p[t, idx[t]], rtol=1e-14)
+    # the bias moves the selection but not the weights of whatever is selected
+    idx_s, w_s = orc.route_topk_biased(lg, k, bias, norm="selected")
+    assert np.array_equal(idx, idx_s)
+    z = np.take_along_axis(lg.astype(np.float64), idx_s.astype(np.int64), axis=1)
+    assert np.allclose(w_s, softmax(z, axis=1), rtol=1e-14)
+    # all experts selected: the "all" weights are the whole softmax and sum to one
+    idx_e, w_e = orc.route_topk_biased(lg, E, bias, norm="all")
+    assert np.allclose(w_e.sum(axis=1), 1.0, rtol=1e-14)
+    # a large bias forces the expert in
+    big = np.zeros(E, np.float32)
+    big[5] = 100.0
+    assert (orc.route_topk_biased(lg, 1, big)[0][:, 0] == 5).all()
+
+
+@pytest.mark.parametrize("norm", ["selected", "all"])
+def test_route_topk_biased_bwd_matches_autograd(norm):
+    import torch
+    rng = np.random.default_rng(42)
+    T, E, k = 50, 7, 3
+    lg = rng.standard_normal((T, E)).astype(np.float32)
+    bias = rng.standard_normal(E).astype(np.float32)
+    dg = rng.standard_normal((T, k))
+    idx, w = orc.route_topk_biased(lg, k, bias, norm)
+    x = torch.tensor(lg.astype(np.float64), requires_grad=True)
+    ti = torch.tensor(idx.astype(np.int64))
+    if norm == "selected":
+        g = torch.softmax(torch.gather(x, 1, ti), dim=1)
+    else:
+        g = torch.gather(torch.softmax(x, dim=1), 1, ti)
+    assert np.allclose(g.detach().numpy(), w, rtol=1e-13)
+    (g * torch.tensor(dg)).sum().backward()
+    got = orc.route_topk_biased_bwd(dg, lg, idx, norm)
+    assert np.allclose(got, x.grad.numpy(), rtol=1e-11, atol=1e-13)
+    if norm == "selected":  # and the established backward agrees
+        assert np.allclose(got, orc.route_topk_bwd(dg, w, idx, E), rtol=1e-12, atol=1e-14)
+
+
+def test_capacity_drop_hand_and_properties():
+    # experts chosen per flat slot: 0 0 1 0 1 1 0 ; capacity 2 -> third and fourth 0 and third 1 are dropped
+    ei = np.array([[0, 0], [1, 0], [1, 1], [0, -1]], np.int32)
+    kept = orc.capacity_drop(ei, 2, 2)
+    assert kept.tolist() == [[0, 0], [1, -1], [1, -1], [-1, -1]]
+    assert np.array_equal(orc.capacity_drop(ei, 2, 100), ei)
+    assert (orc.capacity_drop(ei, 2, 0) == -1).all()
+    rng = np.random.default_rng(43)
+    for _ in range(20):
+        T, k, E = int(rng.integers(1, 60)), int(rng.integers(1, 4)), int(rng.integers(1, 6))
+        ei = rng.integers(-1, E, size=(T, k)).astype(np.int32)
+        cap = int(rng.integers(0, T + 2))
+        kept = orc.capacity_drop(ei, E, cap)
+        flat, kf = ei.reshape(-1), kept.reshape(-1)
+        for e in range(E):
+            chosen = np.flatnonzero(flat == e)
+            survivors = np.flatnonzero(kf == e)
+            assert list(survivors) == list(chosen[:cap])  # the earliest `cap` slots stay
+        assert ((kf == flat) | (kf == -1)).all()
