@@ -95,6 +95,32 @@ int32_t dynmo_route_topk_bwd(const dynmo_desc* d, const float* dgate, const floa
 int32_t dynmo_route_capacity_bwd(const dynmo_desc* d, const float* dgate, const float* scores,
                                  const int32_t* expert_idx, float* dscores, void* stream);
 
+/* Variants of the token-choice routing that the paper's discussion of MoE balancing
+ * names (Sec. 2.1: bias terms added to the token-to-expert affinity scores; Sec. 6:
+ * expert capacity in the GShard / Switch family).
+ *
+ * dynmo_route_topk_ex: like dynmo_route_topk, but the experts are ordered by
+ * logits[t,e] + bias[e] (one fp32 add; bias [E] or NULL) and the gate weights are taken
+ * from the raw logits: DYNMO_NORM_SELECTED = softmax over the k selected logits,
+ * DYNMO_NORM_ALL = softmax over all E logits read at the selected experts.
+ * Backward: dynmo_route_topk_bwd for DYNMO_NORM_SELECTED, dynmo_route_topk_all_bwd
+ * (dlogit[e] = sum_s dgate_s w_s ([e == e_s] - p[e]), p the softmax over all E) for
+ * DYNMO_NORM_ALL.  The selection and the bias carry no gradient. */
+enum { DYNMO_NORM_SELECTED = 0, DYNMO_NORM_ALL = 1 };
+int32_t dynmo_route_topk_ex(const dynmo_desc* d, const float* logits, const float* bias, int32_t gate_norm,
+                            int32_t* expert_idx, float* gate_w, void* stream);
+int32_t dynmo_route_topk_all_bwd(const dynmo_desc* d, const float* dgate, const float* logits,
+                                 const int32_t* expert_idx, float* dlogits, void* stream);
+
+/* Expert capacity with token dropping: slots are served in ascending flat order
+ * t*k + s and a slot whose expert already holds `capacity` slots is dropped:
+ * expert_idx_kept [T,k] = expert_idx, or -1 for a dropped (or already unrouted) slot.
+ * Feed expert_idx_kept to dynmo_permute; keep expert_idx and gate_w for the routing
+ * backward (a dropped slot gets dgate = 0 from dynmo_combine_bwd). */
+size_t dynmo_route_drop_workspace_bytes(const dynmo_desc* d);
+int32_t dynmo_route_drop(const dynmo_desc* d, const int32_t* expert_idx, int32_t capacity,
+                         int32_t* expert_idx_kept, void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- permute ----------------------------------------------------------- */
 
 size_t dynmo_permute_workspace_bytes(const dynmo_desc* d);

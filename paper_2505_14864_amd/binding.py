@@ -46,6 +46,10 @@ SIGNATURES = {
     "dynmo_route_active": (_I, [_D, _P, _I, _P, _P, _P]),
     "dynmo_route_topk_bwd": (_I, [_D, _P, _P, _P, _P, _P]),
     "dynmo_route_capacity_bwd": (_I, [_D, _P, _P, _P, _P, _P]),
+    "dynmo_route_topk_ex": (_I, [_D, _P, _P, _I, _P, _P, _P]),
+    "dynmo_route_topk_all_bwd": (_I, [_D, _P, _P, _P, _P, _P]),
+    "dynmo_route_drop_workspace_bytes": (C.c_size_t, [_D]),
+    "dynmo_route_drop": (_I, [_D, _P, _I, _P, _P, C.c_size_t, _P]),
     "dynmo_permute_workspace_bytes": (C.c_size_t, [_D]),
     "dynmo_permute": (_I, [_D, _P, _P, _P, _P, _P, _P, _P, C.c_size_t, _P]),
     "dynmo_permute_bwd": (_I, [_D, _P, _P, _P, _P, _P]),
@@ -143,6 +147,28 @@ def dynmo_route_topk_bwd(d, dgate, gate_w, expert_idx, dlogits, stream=None):
 def dynmo_route_capacity_bwd(d, dgate, scores, expert_idx, dscores, stream=None):
     _check("dynmo_route_capacity_bwd", lib().dynmo_route_capacity_bwd(C.byref(d), _ptr(dgate), _ptr(scores),
                                                                       _ptr(expert_idx), _ptr(dscores), _stream(stream)))
+
+
+NORM_SELECTED, NORM_ALL = 0, 1
+
+
+def dynmo_route_topk_ex(d, logits, bias, gate_norm, expert_idx, gate_w, stream=None):
+    _check("dynmo_route_topk_ex", lib().dynmo_route_topk_ex(C.byref(d), _ptr(logits), _ptr(bias), int(gate_norm),
+                                                            _ptr(expert_idx), _ptr(gate_w), _stream(stream)))
+
+
+def dynmo_route_topk_all_bwd(d, dgate, logits, expert_idx, dlogits, stream=None):
+    _check("dynmo_route_topk_all_bwd", lib().dynmo_route_topk_all_bwd(C.byref(d), _ptr(dgate), _ptr(logits),
+                                                                      _ptr(expert_idx), _ptr(dlogits), _stream(stream)))
+
+
+def dynmo_route_drop_workspace_bytes(d):
+    return int(lib().dynmo_route_drop_workspace_bytes(C.byref(d)))
+
+
+def dynmo_route_drop(d, expert_idx, capacity, expert_idx_kept, workspace, stream=None):
+    _check("dynmo_route_drop", lib().dynmo_route_drop(C.byref(d), _ptr(expert_idx), int(capacity), _ptr(expert_idx_kept),
+                                                      _ptr(workspace), workspace.numel(), _stream(stream)))
 
 
 def dynmo_permute_workspace_bytes(d):

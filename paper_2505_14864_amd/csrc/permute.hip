@@ -282,6 +282,55 @@ extern "C" int32_t dynmo_permute(const dynmo_desc* d, const void* x, const int32
   return launch_rows<kMaxExperts>(d, x, dst_pos, x_p, st);
 }
 
+namespace dynmo {
+// kept[i] = expert_idx[i] if fewer than `capacity` earlier slots chose the same expert
+// (the slot's rank inside its expert segment is its row minus the segment's first row)
+__global__ void route_drop_kernel(const int32_t* __restrict__ expert_idx, const int32_t* __restrict__ seg,
+                                  const int32_t* __restrict__ dst_pos, int32_t* __restrict__ kept, int n_slots, int E,
+                                  int capacity) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_slots) return;
+  const int e = expert_idx[i];
+  int out = -1;
+  if (e >= 0 && e < E && dst_pos[i] - seg[e] < capacity) out = e;
+  kept[i] = out;
+}
+
+static size_t drop_index_bytes(const dynmo_desc* d) {  // seg_offsets, src_slot, dst_pos of the ranking pass
+  return align_up(((size_t)d->E + 1 + 2 * (size_t)d->T * d->k) * sizeof(int32_t), 256);
+}
+}  // namespace dynmo
+
+extern "C" size_t dynmo_route_drop_workspace_bytes(const dynmo_desc* d) {
+  if (check_desc(d)) return 0;
+  return dynmo_permute_workspace_bytes(d) + drop_index_bytes(d) + 256;
+}
+
+extern "C" int32_t dynmo_route_drop(const dynmo_desc* d, const int32_t* expert_idx, int32_t capacity,
+                                    int32_t* expert_idx_kept, void* workspace, size_t workspace_bytes, void* stream) {
+  int32_t rc = check_desc(d);
+  if (rc) return rc;
+  if (!expert_idx || !expert_idx_kept || !workspace || capacity < 0) return DYNMO_EINVAL;
+  if (workspace_bytes < dynmo_route_drop_workspace_bytes(d)) return DYNMO_EWORKSPACE;
+  const int n_slots = d->T * d->k;
+  if (n_slots == 0) return DYNMO_OK;
+  // The stable ranking the permutation uses gives every slot its rank among the slots
+  // of its expert in ascending slot order; a slot is kept while that rank is below the capacity.
+  char* base = (char*)align_up((size_t)workspace, 256);
+  int32_t* seg = (int32_t*)base;
+  int32_t* src_slot = seg + d->E + 1;
+  int32_t* dst_pos = src_slot + n_slots;
+  void* ws = base + drop_index_bytes(d);
+  rc = dynmo_permute(d, nullptr, expert_idx, nullptr, seg, src_slot, dst_pos, ws, dynmo_permute_workspace_bytes(d),
+                     stream);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  route_drop_kernel<<<dim3((n_slots + 255) / 256), dim3(256), 0, st>>>(expert_idx, seg, dst_pos, expert_idx_kept, n_slots,
+                                                                      d->E, capacity);
+  DYNMO_LAUNCH_CHECK();
+  return DYNMO_OK;
+}
+
 extern "C" int32_t dynmo_permute_bwd(const dynmo_desc* d, const void* dx_p, const int32_t* dst_pos, const void* dbase,
                                      void* dx, void* stream) {
   int32_t rc = check_desc(d);

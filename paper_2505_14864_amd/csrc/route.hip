@@ -61,6 +61,65 @@ __global__ __launch_bounds__(256) void route_topk_kernel(const float* __restrict
   }
 }
 
+// The same selection with its two variants: the order is taken on logit + bias (one
+// fp32 add; the bias steers the selection only), and the gate weights come from the raw
+// logits as the softmax over the selected ones or over all E.  Same lane layout.
+struct CandRaw {
+  float v;    // logit + bias: what the order is taken on
+  float raw;  // the logit itself
+  int idx;
+};
+
+template <int LPT>
+__global__ __launch_bounds__(256) void route_topk_ex_kernel(const float* __restrict__ logits, const float* __restrict__ bias,
+                                                            int norm_all, int32_t* __restrict__ expert_idx,
+                                                            float* __restrict__ gate_w, int T, int E, int k) {
+  constexpr int TOK_PER_WAVE = 64 / LPT;
+  const int lane = threadIdx.x & 63;
+  const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int j = lane % LPT;
+  const long t = (long)wave * TOK_PER_WAVE + lane / LPT;
+  const bool live = t < T && j < E;
+  const float raw = live ? logits[t * E + j] : 0.f;
+  CandRaw mine;
+  mine.raw = raw;
+  mine.v = live ? (bias ? raw + bias[j] : raw) : 0.f;
+  mine.idx = live ? j : 0x7fffffff;
+  float my_raw = 0.f;
+  int my_idx = 0;
+  for (int s = 0; s < k; ++s) {
+    CandRaw best = mine;
+#pragma unroll
+    for (int m = 1; m < LPT; m <<= 1) {
+      CandRaw o;
+      o.v = __shfl_xor(best.v, m, 64);
+      o.raw = __shfl_xor(best.raw, m, 64);
+      o.idx = __shfl_xor(best.idx, m, 64);
+      const Cand a = {o.v, o.idx}, b = {best.v, best.idx};
+      if (better(a, b)) best = o;
+    }
+    if (j == s) {
+      my_raw = best.raw;
+      my_idx = best.idx;
+    }
+    if (mine.idx == best.idx) mine.idx = 0x7fffffff;  // retire the winner
+  }
+  // softmax statistics over the token's lanes: lane j < k holds slot j's logit; for the
+  // all-expert normalisation lane j < E contributes its own logit instead
+  const bool in_sum = norm_all ? live : (t < T && j < k);
+  const float z = norm_all ? raw : my_raw;
+  float mx = in_sum ? z : -INFINITY;
+#pragma unroll
+  for (int m = 1; m < LPT; m <<= 1) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+  float sum = in_sum ? __expf(z - mx) : 0.f;
+#pragma unroll
+  for (int m = 1; m < LPT; m <<= 1) sum += __shfl_xor(sum, m, 64);
+  if (t < T && j < k) {
+    expert_idx[t * k + j] = my_idx;
+    gate_w[t * k + j] = __expf(my_raw - mx) / sum;
+  }
+}
+
 // ---------------------------------------------------------------------------
 // Capacity top-k: one workgroup per sequence.  A 4-pass, 8-bit-per-pass radix
 // select on order-preserving integer keys finds the cap-th largest score; ties
@@ -185,6 +244,31 @@ __global__ void route_topk_bwd_kernel(const float* __restrict__ dgate, const flo
   }
 }
 
+// Backward of the all-expert normalisation: with p = softmax(logits) over all E and
+// w_s = p[e_s], dlogit[e] = sum_s dgate_s w_s ([e == e_s] - p[e]).  One thread per token.
+__global__ void route_topk_all_bwd_kernel(const float* __restrict__ dgate, const float* __restrict__ logits,
+                                          const int32_t* __restrict__ expert_idx, float* __restrict__ dlogits, int T,
+                                          int E, int k) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= T) return;
+  const float* lg = logits + (long)t * E;
+  float mx = lg[0];
+  for (int e = 1; e < E; ++e) mx = fmaxf(mx, lg[e]);
+  float sum = 0.f;
+  for (int e = 0; e < E; ++e) sum += __expf(lg[e] - mx);
+  const float inv = 1.f / sum;
+  float inner = 0.f;
+  for (int s = 0; s < k; ++s) {
+    const int e = expert_idx[(long)t * k + s];
+    if (e >= 0 && e < E) inner += dgate[(long)t * k + s] * __expf(lg[e] - mx) * inv;
+  }
+  for (int e = 0; e < E; ++e) dlogits[(long)t * E + e] = -__expf(lg[e] - mx) * inv * inner;
+  for (int s = 0; s < k; ++s) {
+    const int e = expert_idx[(long)t * k + s];
+    if (e >= 0 && e < E) dlogits[(long)t * E + e] += dgate[(long)t * k + s] * __expf(lg[e] - mx) * inv;
+  }
+}
+
 __global__ void route_capacity_bwd_kernel(const float* __restrict__ dgate, const float* __restrict__ scores,
                                           const int32_t* __restrict__ expert_idx, float* __restrict__ dscores, int T) {
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
@@ -207,9 +291,51 @@ static int32_t launch_topk(const dynmo_desc* d, const float* logits, int32_t* ei
   return DYNMO_OK;
 }
 
+template <int LPT>
+static int32_t launch_topk_ex(const dynmo_desc* d, const float* logits, const float* bias, int norm_all, int32_t* ei,
+                              float* gw, hipStream_t st) {
+  const long tok_per_block = (256 / 64) * (64 / LPT);
+  const long blocks = (d->T + tok_per_block - 1) / tok_per_block;
+  if (blocks > 0) {
+    DYNMO_TIMED_LAUNCH(K_ROUTE_TOPK, st, route_topk_ex_kernel<LPT><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(
+        logits, bias, norm_all, ei, gw, d->T, d->E, d->k));
+  }
+  return DYNMO_OK;
+}
+
 }  // namespace dynmo
 
 using namespace dynmo;
+
+extern "C" int32_t dynmo_route_topk_ex(const dynmo_desc* d, const float* logits, const float* bias, int32_t gate_norm,
+                                       int32_t* expert_idx, float* gate_w, void* stream) {
+  int32_t rc = check_desc(d);
+  if (rc) return rc;
+  if (!logits || !expert_idx || !gate_w || (gate_norm != DYNMO_NORM_SELECTED && gate_norm != DYNMO_NORM_ALL))
+    return DYNMO_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  const int E = d->E, all = gate_norm == DYNMO_NORM_ALL;
+  if (E <= 1) return launch_topk_ex<1>(d, logits, bias, all, expert_idx, gate_w, st);
+  if (E <= 2) return launch_topk_ex<2>(d, logits, bias, all, expert_idx, gate_w, st);
+  if (E <= 4) return launch_topk_ex<4>(d, logits, bias, all, expert_idx, gate_w, st);
+  if (E <= 8) return launch_topk_ex<8>(d, logits, bias, all, expert_idx, gate_w, st);
+  if (E <= 16) return launch_topk_ex<16>(d, logits, bias, all, expert_idx, gate_w, st);
+  if (E <= 32) return launch_topk_ex<32>(d, logits, bias, all, expert_idx, gate_w, st);
+  return launch_topk_ex<64>(d, logits, bias, all, expert_idx, gate_w, st);
+}
+
+extern "C" int32_t dynmo_route_topk_all_bwd(const dynmo_desc* d, const float* dgate, const float* logits,
+                                            const int32_t* expert_idx, float* dlogits, void* stream) {
+  int32_t rc = check_desc(d);
+  if (rc) return rc;
+  if (!dgate || !logits || !expert_idx || !dlogits) return DYNMO_EINVAL;
+  if (d->T > 0) {
+    DYNMO_TIMED_LAUNCH(K_ROUTE_TOPK_BWD, (hipStream_t)stream,
+                       route_topk_all_bwd_kernel<<<dim3((d->T + 255) / 256), dim3(256), 0, (hipStream_t)stream>>>(
+                           dgate, logits, expert_idx, dlogits, d->T, d->E, d->k));
+  }
+  return DYNMO_OK;
+}
 
 extern "C" int32_t dynmo_route_topk(const dynmo_desc* d, const float* logits, int32_t* expert_idx, float* gate_w,
                                     void* stream) {

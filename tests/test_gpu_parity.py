@@ -512,3 +512,82 @@ def test_forward_with_fused_gather(mode, w):
     else:
         ref = orc.mod_layer(f["scores"], w.cap, f["x"], f["Wg"], f["Wu"], f["Wd"], f["dout"])
     assert_close("out", to_host(b.out), ref["out"], TOL[w.dtype])
+
+
+@pytest.mark.parametrize("T,E,k", [(1, 1, 1), (300, 6, 3), (1000, 8, 2), (513, 16, 4), (257, 64, 8), (64, 5, 5)])
+@pytest.mark.parametrize("norm", ["selected", "all"])
+def test_route_topk_variants(T, E, k, norm):
+    """Biased selection and the two gate normalisations: indices bit-exact (ties and the
+    fp32 logit + bias sum included), weights and the all-expert backward in fp32."""
+    say("route_topk_ex T=%d E=%d k=%d %s" % (T, E, k, norm))
+    rng = np.random.default_rng(700 + T + E)
+    lg = rng.standard_normal((T, E)).astype(np.float32)
+    if E > 2:
+        lg[::5, 1] = lg[::5, E - 1]          # exact ties
+        lg[::9] = np.round(lg[::9] * 4) / 4  # many equal values
+    bias = (rng.standard_normal(E) * 0.5).astype(np.float32)
+    bias[0] = 0.0
+    d = B.make_desc(T, 8, 8, E, k, "f32")
+    ei = torch.empty((T, k), dtype=torch.int32, device="cuda")
+    gw = torch.empty((T, k), dtype=torch.float32, device="cuda")
+    dl = torch.empty((T, E), dtype=torch.float32, device="cuda")
+    code = B.NORM_SELECTED if norm == "selected" else B.NORM_ALL
+    for use_bias in (True, False):
+        b = bias if use_bias else None
+        B.dynmo_route_topk_ex(d, to_device(lg), to_device(bias) if use_bias else None, code, ei, gw)
+        ref_i, ref_w = orc.route_topk_biased(lg, k, b, norm)
+        assert np.array_equal(to_host(ei), ref_i)
+        assert_close("gate_w", to_host(gw), ref_w, 1e-5)
+        dg = rng.standard_normal((T, k)).astype(np.float32)
+        if norm == "all":
+            B.dynmo_route_topk_all_bwd(d, to_device(dg), to_device(lg), ei, dl)
+        else:
+            B.dynmo_route_topk_bwd(d, to_device(dg), gw, ei, dl)
+        assert_close("dlogits", to_host(dl), orc.route_topk_biased_bwd(dg, lg, ref_i, norm), 1e-4)
+
+
+@pytest.mark.parametrize("T,E,k,cap", [(1, 1, 1, 0), (50, 4, 2, 7), (3000, 8, 2, 300), (1500, 16, 4, 100000),
+                                       (2500, 3, 1, 1)])
+def test_route_drop(T, E, k, cap):
+    say("route_drop T=%d E=%d k=%d cap=%d" % (T, E, k, cap))
+    rng = np.random.default_rng(800 + T)
+    ei = rng.integers(-1 if k == 1 else 0, E, size=(T, k)).astype(np.int32)
+    d = B.make_desc(T, 8, 8, E, k, "f32")
+    kept = torch.full((T, k), 77, dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.dynmo_route_drop_workspace_bytes(d), dtype=torch.uint8, device="cuda")
+    B.dynmo_route_drop(d, to_device(ei), cap, kept, ws)
+    assert np.array_equal(to_host(kept), orc.capacity_drop(ei, E, cap))
+
+
+def test_moe_layer_with_expert_capacity():
+    """Biased selection + capacity dropping + the whole layer, forward and backward: a
+    dropped slot contributes nothing to the output and gets dgate = 0, while the routing
+    backward still sees its weight."""
+    say("moe layer with capacity")
+    w = wl.scaled(wl.CONFIGS[2], T=600, H=128, F=192, E=8, k=2, seed=71)
+    inp = wl.make_inputs(w, threads=1)
+    f = f32_inputs(inp)
+    bias = np.linspace(0.4, -0.4, w.E).astype(np.float32)
+    cap = 120  # 1200 slots over 8 experts: the popular experts overflow
+    layer = RoutedFFNLayer(w.T, w.H, w.F, w.E, w.k, w.dtype, "moe")
+    dev = {n: to_device(a) for n, a in inp.items()}
+    chosen = torch.empty((w.T, w.k), dtype=torch.int32, device="cuda")
+    B.dynmo_route_topk_ex(layer.d, dev["logits"], to_device(bias), B.NORM_SELECTED, chosen, layer.gate_w)
+    ws = torch.empty(B.dynmo_route_drop_workspace_bytes(layer.d), dtype=torch.uint8, device="cuda")
+    B.dynmo_route_drop(layer.d, chosen, cap, layer.expert_idx, ws)
+    layer.forward(dev["x"], dev["Wg"], dev["Wu"], dev["Wd"])
+    layer.backward(dev["dout"], dev["Wg"], dev["Wu"], dev["Wd"])
+    B.dynmo_route_topk_bwd(layer.d, layer.dgate, layer.gate_w, chosen, layer.droute)
+    torch.cuda.synchronize()
+    idx, gate = orc.route_topk_biased(f["logits"], w.k, bias, "selected")
+    kept = orc.capacity_drop(idx, w.E, cap)
+    assert (kept == -1).sum() > 50 and np.array_equal(to_host(layer.expert_idx), kept)
+    fwd = orc.layer_fwd(f["x"], kept, gate, f["Wg"], f["Wu"], f["Wd"], residual=False)
+    bwd = orc.layer_bwd(f["dout"], fwd, gate, f["Wg"], f["Wu"], f["Wd"], residual=False)
+    ref = dict(**fwd, **bwd)
+    check_layer_full(layer, ref, w.dtype)
+    counts, _ = layer.load()
+    assert max(counts) <= cap and sum(counts) == int((kept >= 0).sum())
+    assert not to_host(layer.dgate)[kept < 0].any()
+    assert_close("dlogits", to_host(layer.droute), orc.route_topk_biased_bwd(bwd["dgate"], f["logits"], idx, "selected"),
+                 TOL[w.dtype])
