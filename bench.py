@@ -4,7 +4,10 @@
 A step is one pass of the whole hot path over one batch of synthetic input:
 route -> permute -> grouped FFN fwd -> combine -> combine bwd -> grouped FFN bwd
 -> permute bwd -> route bwd -> layer_load -> host Partition call.
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value (routed tokens/s, inputs resident in HBM), ms_per_step,
+roofline (the dominant kernel against its published peak, from event durations taken inside
+the timed region), cpu_baseline (the oracle on a bounded sample), the per-kernel list and the
+imbalance of the exported loads before and after the Partition balancer.
 """
 import argparse
 import json
