@@ -626,17 +626,23 @@ __global__ __launch_bounds__(256) void ffn_split_reduce_kernel(const float* __re
   // chunk c of split tile u was run by workgroup (u % slots) of XCD (u / slots) * split + c
   const float* src = partial + (size_t)((u % slots) * kXcds + (u / slots) * split) * kPartialFloats;
   const int col = (threadIdx.x & 63) * 4;
-#pragma unroll 4
+#pragma unroll 2
   for (int it = 0; it < 16; ++it) {
     const int rl = quarter * 64 + it * 4 + (threadIdx.x >> 6);
-    float4 sum = *(const float4*)(src + rl * BN + col);
-    for (int c = 1; c < split; ++c) {
-      const float4 v = *(const float4*)(src + (size_t)c * kPartialFloats + rl * BN + col);
-      sum.x += v.x;
-      sum.y += v.y;
-      sum.z += v.z;
-      sum.w += v.w;
-    }
+    // all chunks' loads are issued before the first add; the sum runs in chunk order
+    float4 v[kXcds];
+#pragma unroll
+    for (int c = 0; c < kXcds; ++c)
+      if (c < split) v[c] = *(const float4*)(src + (size_t)c * kPartialFloats + rl * BN + col);
+    float4 sum = v[0];
+#pragma unroll
+    for (int c = 1; c < kXcds; ++c)
+      if (c < split) {
+        sum.x += v[c].x;
+        sum.y += v[c].y;
+        sum.z += v[c].z;
+        sum.w += v[c].w;
+      }
     const int row = m0 + rl;
     if (row < m_end && n0 + col < N) {
       uint2 o;
