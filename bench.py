@@ -557,8 +557,8 @@ def cpu_baseline(w, inp, sample_tokens):
         threads = os.cpu_count() or 1
     flops_per_row = 18.0 * w.H * w.F
     if sample_tokens <= 0:
-        # aim at roughly 5e12 flop of float64 work (10-30 s on the machine's host cores)
-        rows_target = max(64.0, 5e12 / flops_per_row)
+        # aim at roughly 1e13 flop of float64 work (10-30 s on the machine's host cores)
+        rows_target = max(64.0, 1e13 / flops_per_row)
         frac_routed = {"moe": w.k, "mod": (w.cap / w.S) if w.S else 1.0, "early_exit": 2.5}[w.mode]
         sample_tokens = int(min(w.T, max(64, rows_target / frac_routed)))
         if w.mode == "mod":
