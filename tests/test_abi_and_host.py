@@ -56,6 +56,35 @@ def test_bad_arguments_are_rejected_without_a_gpu():
     assert lib.dynmo_permute_workspace_bytes(B.C.byref(d)) == 0
     with pytest.raises(B.DynmoError):
         B.dynmo_partition([1.0, -2.0], 2)
+    d = B.make_desc(8, 16, 16, 4, 2, "bf16")
+    assert lib.dynmo_route_topk_ex(B.C.byref(d), None, None, 0, None, None, None) == -1
+    assert lib.dynmo_route_topk_all_bwd(B.C.byref(d), None, None, None, None, None) == -1
+    assert lib.dynmo_route_drop(B.C.byref(d), None, 4, None, None, 0, None) == -1
+    assert lib.dynmo_grouped_ffn_fwd_gather(B.C.byref(d), None, None, None, None, None, None, None, None, None, None, 0,
+                                            None) == -1
+    assert lib.dynmo_peak_copy(None, None, 16, None) == -1
+    assert lib.dynmo_peak_mfma_bf16(0, None, None, None, None) == -1
+    assert lib.dynmo_route_drop_workspace_bytes(B.C.byref(d)) > lib.dynmo_permute_workspace_bytes(B.C.byref(d))
+    for bad in ([0, 2, 2, 5], [1, 2], [0, 3, 1, 2]):  # wrong end, wrong start, not monotone
+        with pytest.raises(B.DynmoError):
+            B.dynmo_diffusion([1.0, 2.0], bad)
+    with pytest.raises(B.DynmoError):
+        B.dynmo_diffusion([1.0, float("nan")], [0, 1, 2])
+    with pytest.raises(B.DynmoError):
+        B.dynmo_repack([1, 1], [1.0, 1.0], [1, -1], 1, 10.0)
+
+
+def test_diffusion_and_repack_edge_cases():
+    assert B.dynmo_diffusion([5.0], [0, 1]) == ([0, 1], 0, 0.0, 0.0)
+    assert B.dynmo_diffusion([5.0, 3.0], [0, 1, 2]) == ([0, 1, 2], 0, 2.0, 2.0)  # one layer each: nothing may move
+    # a stage that starts empty is filled (phi 6 -> 4 -> 0), exactly as the oracle does it
+    b, rounds, phi0, phi1 = B.dynmo_diffusion([1.0, 2.0, 3.0], [0, 0, 3])
+    rb, rh = orc.diffusion_balance([1.0, 2.0, 3.0], [0, 0, 3])
+    assert (b, rounds, phi0, phi1) == (list(rb), len(rh) - 1, rh[0], rh[-1]) == ([0, 2, 3], 2, 6.0, 0.0)
+    assert B.dynmo_potential([7.0]) == 0.0
+    assert B.dynmo_repack([], [], [], 0, 1.0) == ([], [], [], [])
+    # nothing to do when the target is already met
+    assert B.dynmo_repack([1, 0, 1], [1.0, 9.0, 1.0], [2, 0, 2], 2, 10.0) == ([], [1, 0, 1], [1.0, 9.0, 1.0], [2, 0, 2])
 
 
 def read_golden(path):
