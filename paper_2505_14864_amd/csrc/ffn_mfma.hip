@@ -22,6 +22,10 @@
 // no host synchronisation is needed.  One persistent workgroup per compute unit
 // walks the tile list; each XCD (workgroup ids congruent modulo 8) takes a share
 // balanced by cost, ordered so that neighbours share operand tiles in that XCD's L2.
+// Wavefronts with no valid rows or columns in a ragged tile skip their MFMAs.  When the
+// last round of a row-segmented product would fill at most half of the chip, its tiles
+// are split along k over several XCDs and a small second kernel adds the fp32 partial
+// tiles in a fixed order (ffn_split_reduce_kernel).
 #include <type_traits>
 #include <utility>
 
