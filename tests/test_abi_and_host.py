@@ -185,3 +185,34 @@ def test_repack_matches_oracle():
     with pytest.raises(B.DynmoError) as e:
         B.dynmo_repack([1, 1, 1, 1], [3, 4, 2, 6], [2, 3, 1, 2], 2, 10, capacity=1)
     assert e.value.status == -3
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_bench_work_model():
+    """The algorithmic work bench.py divides by: flops of the seven products add up to
+    18 H F per routed row, and the row movers count each row once per direction."""
+    import importlib.util
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    spec = importlib.util.spec_from_file_location("bench_mod", os.path.join(root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    from paper_2505_14864_amd import workloads as wl
+    w = wl.CONFIGS[2]
+    R = w.T * w.k
+    flops = sum(bench.kernel_work(n, w, R, w.T)[1] for n in
+                ("ffn_gateup", "ffn_down", "ffn_dA", "ffn_dX", "ffn_dWd", "ffn_dWg", "ffn_dWu"))
+    assert flops == 18.0 * w.H * w.F * R
+    assert bench.kernel_work("permute_rows", w, R, w.T) == ("hbm", (w.T + R) * w.H * 2 + 4.0 * w.T * w.k)
+    assert bench.kernel_work("combine", w, R, w.T)[1] == (R + w.T) * w.H * 2 + 8.0 * w.T * w.k
+    w4 = wl.CONFIGS[4]  # residual mode: the pass-through base is read too
+    R4 = w4.B * w4.cap
+    assert bench.kernel_work("combine", w4, R4, w4.T)[1] == (R4 + 2 * w4.T) * w4.H * 2 + 8.0 * w4.T
+    assert bench.kernel_work("route_topk", w, R, w.T) is None
