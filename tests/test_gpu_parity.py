@@ -591,3 +591,39 @@ def test_moe_layer_with_expert_capacity():
     assert not to_host(layer.dgate)[kept < 0].any()
     assert_close("dlogits", to_host(layer.droute), orc.route_topk_biased_bwd(bwd["dgate"], f["logits"], idx, "selected"),
                  TOL[w.dtype])
+
+
+def test_moe_full_size_capacity_and_gather():
+    """Config 2 at full size through the variants: biased selection, expert capacity that
+    makes the two popular experts overflow, the whole layer checked on samples against the
+    oracle; then the gather-fused forward must reproduce the copied-rows forward bit for bit."""
+    w = wl.CONFIGS[2]
+    say("full-size config 2 with capacity and fused gather")
+    inp = wl.make_inputs(w, threads=16)
+    f = f32_inputs(inp)
+    dev = {n: to_device(a) for n, a in inp.items()}
+    bias = np.linspace(0.05, -0.05, w.E).astype(np.float32)
+    cap = 1100
+    layer = RoutedFFNLayer(w.T, w.H, w.F, w.E, w.k, w.dtype, "moe")
+    chosen = torch.empty((w.T, w.k), dtype=torch.int32, device="cuda")
+    B.dynmo_route_topk_ex(layer.d, dev["logits"], to_device(bias), B.NORM_SELECTED, chosen, layer.gate_w)
+    ws = torch.empty(B.dynmo_route_drop_workspace_bytes(layer.d), dtype=torch.uint8, device="cuda")
+    B.dynmo_route_drop(layer.d, chosen, cap, layer.expert_idx, ws)
+    layer.forward(dev["x"], dev["Wg"], dev["Wu"], dev["Wd"])
+    layer.backward(dev["dout"], dev["Wg"], dev["Wu"], dev["Wd"])
+    torch.cuda.synchronize()
+    idx, gate = orc.route_topk_biased(f["logits"], w.k, bias, "selected")
+    kept = orc.capacity_drop(idx, w.E, cap)
+    assert np.array_equal(to_host(chosen), idx) and np.array_equal(to_host(layer.expert_idx), kept)
+    counts, _ = layer.load()
+    assert max(counts) == cap and sum(counts) == int((kept >= 0).sum()) < w.T * w.k
+    check_layer_sampled(layer, f, kept, gate, False, w.dtype, np.random.default_rng(91))
+    other = RoutedFFNLayer(w.T, w.H, w.F, w.E, w.k, w.dtype, "moe")
+    other.expert_idx.copy_(layer.expert_idx)
+    other.gate_w.copy_(layer.gate_w)
+    other.forward_gather(dev["x"], dev["Wg"], dev["Wu"], dev["Wd"])
+    torch.cuda.synchronize()
+    R = sum(counts)
+    for n in ("G", "U", "y_p"):
+        assert torch.equal(getattr(layer, n)[:R], getattr(other, n)[:R]), n
+    assert torch.equal(layer.out, other.out)
