@@ -627,3 +627,20 @@ def test_moe_full_size_capacity_and_gather():
     for n in ("G", "U", "y_p"):
         assert torch.equal(getattr(layer, n)[:R], getattr(other, n)[:R]), n
     assert torch.equal(layer.out, other.out)
+
+
+@pytest.mark.parametrize("H,F", [(512, 1536), (256, 4096), (768, 2048)])
+def test_split_last_round_small_problem(H, F):
+    """Few output tiles and a long contraction: the down and dX products split their tiles
+    along k over the XCDs (for F = 1536 into three chunks, the middle one straddling the
+    two phases of dX) and a second pass sums the partial tiles; full check against the oracle."""
+    say("split-k small problem H=%d F=%d" % (H, F))
+    w = wl.scaled(wl.CONFIGS[2], T=330, H=H, F=F, E=2, k=1, seed=81)
+    inp = wl.make_inputs(w, threads=4)
+    layer = run_moe(w, inp)
+    f = f32_inputs(inp)
+    ref = orc.moe_layer(f["logits"], f["x"], f["Wg"], f["Wu"], f["Wd"], w.k, f["dout"])
+    check_layer_full(layer, ref, w.dtype)
+    again = run_moe(w, inp)  # the split sums in a fixed order: bit-identical from run to run
+    for n in ("y_p", "dx_p", "out", "dx"):
+        assert torch.equal(getattr(layer, n), getattr(again, n)), n
