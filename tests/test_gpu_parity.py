@@ -644,3 +644,59 @@ def test_split_last_round_small_problem(H, F):
     again = run_moe(w, inp)  # the split sums in a fixed order: bit-identical from run to run
     for n in ("y_p", "dx_p", "out", "dx"):
         assert torch.equal(getattr(layer, n), getattr(again, n)), n
+
+
+def test_layer_under_graph_capture():
+    """Forward + backward of a layer captured into a HIP graph (no call on the path
+    allocates, synchronises or issues a memset) and replayed three times with eager work
+    and synchronisations in between; every replay must reproduce the eager results bit
+    for bit, also after the inputs changed in place."""
+    say("graph capture")
+    w = wl.scaled(wl.CONFIGS[2], T=900, H=256, F=2048, E=4, k=2, seed=95)  # down and dX split their tiles
+    inp = wl.make_inputs(w, threads=2)
+    dev = {n: to_device(a) for n, a in inp.items()}
+    layer = RoutedFFNLayer(w.T, w.H, w.F, w.E, w.k, w.dtype, "moe")
+    layer.alloc_backward()
+    names = ("expert_idx", "gate_w", "seg_offsets", "dst_pos", "y_p", "G", "U", "out", "dgate", "dx", "dWg", "dWu", "dWd",
+             "droute")
+
+    def run():
+        layer.route_topk(dev["logits"])
+        layer.forward(dev["x"], dev["Wg"], dev["Wu"], dev["Wd"])
+        layer.backward(dev["dout"], dev["Wg"], dev["Wu"], dev["Wd"])
+        layer.route_bwd()
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return {n: getattr(layer, n).clone() for n in names}
+
+    B.dynmo_profile_enable(False)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        run()  # warm-up outside the capture (function attributes are set on first use)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run()
+    x0, l0 = dev["x"].clone(), dev["logits"].clone()
+    for trial in range(3):
+        if trial == 1:  # new inputs, written in place: the graph reads the same buffers
+            dev["x"].copy_(torch.roll(x0, 7, dims=0))
+            dev["logits"].copy_(torch.roll(l0, 3, dims=1))
+        if trial == 2:
+            dev["x"].copy_(x0)
+            dev["logits"].copy_(l0)
+        run()
+        eager = snapshot()
+        for n in names:
+            if getattr(layer, n).dtype.is_floating_point:
+                getattr(layer, n).fill_(-3.0)
+            else:
+                getattr(layer, n).fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        replayed = snapshot()
+        R = int(eager["seg_offsets"][-1])
+        for n in names:
+            a, b = (eager[n][:R], replayed[n][:R]) if n in ("y_p", "G", "U") else (eager[n], replayed[n])
+            assert torch.equal(a, b), "%s differs on replay %d" % (n, trial)
