@@ -426,6 +426,30 @@ def protocol(a, w, inp, dev, layers, Ws, step):
         fwd_only()
     out["fwd_chain"] = _stats([timed(fwd_only) for _ in range(reps)])
 
+    # ---- the same forward+backward kernels replayed as one HIP graph (no launch gaps;
+    # the load export and the host balancer are not part of it)
+    def device_part():
+        fwd_only()
+        g = dev["dout"]
+        for i in range(L - 1, -1, -1):
+            g = layers[i].backward(g, *Ws[i])
+            if w.mode == "moe":
+                layers[i].route_bwd()
+            elif w.mode == "mod":
+                layers[i].route_bwd(dev["scores"])
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        device_part()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        device_part()
+    for _ in range(3):
+        graph.replay()
+    out["fwd_bwd_graph_replay"] = _stats([timed(graph.replay) for _ in range(reps)])
+    out["fwd_bwd_eager_device_part"] = _stats([timed(device_part) for _ in range(reps)])
+    del graph
+
     # ---- the HBM-bound calls alone, warm (back to back) and cold (caches evicted first)
     if L == 1:
         l0 = layers[0]
@@ -523,6 +547,10 @@ def protocol_text(d, a):
           "  forward          median %.1f  min %.1f" % (f["median_us"], f["min_us"]),
           "  forward+backward median %.1f  min %.1f   -> %.0f routed rows/s" % (
               b["median_us"], b["min_us"], b["routed_rows_per_s"])]
+    if "fwd_bwd_graph_replay" in d:
+        g_, e_ = d["fwd_bwd_graph_replay"], d["fwd_bwd_eager_device_part"]
+        L.append("  its kernels alone (no load export, no host balancer): launched one by one median %.1f, replayed as "
+                 "one HIP graph median %.1f" % (e_["median_us"], g_["median_us"]))
     if "hbm_calls_alone" in d:
         L += ["", "HBM-bound calls alone: warm = back to back, cold = after a 1 GiB fill that evicts L2 and the "
                   "Infinity Cache",
