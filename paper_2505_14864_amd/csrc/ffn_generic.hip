@@ -206,9 +206,15 @@ static int32_t bwd_generic_t(const dynmo_desc* d, const void* dy_p, const void* 
         nullptr, nullptr, nullptr, nullptr));
   }
   // The weight gradients are written for every expert, rows or not.
-  DYNMO_TIMED_LAUNCH(K_FFN_DWD, st, dw_generic_kernel<T><<<dim3(tf, th, d->E), dim3(256), 0, st>>>(seg, d->H, d->F, (const T*)dy_p, (const T*)A, (T*)dWd));
-  DYNMO_TIMED_LAUNCH(K_FFN_DWG, st, dw_generic_kernel<T><<<dim3(th, tf, d->E), dim3(256), 0, st>>>(seg, d->F, d->H, (const T*)dG, (const T*)x_p, (T*)dWg));
-  DYNMO_TIMED_LAUNCH(K_FFN_DWU, st, dw_generic_kernel<T><<<dim3(th, tf, d->E), dim3(256), 0, st>>>(seg, d->F, d->H, (const T*)dU, (const T*)x_p, (T*)dWu));
+  DYNMO_TIMED_LAUNCH(K_FFN_DWD, st,
+                     dw_generic_kernel<T><<<dim3(tf, th, d->E), dim3(256), 0, st>>>(seg, d->H, d->F, (const T*)dy_p,
+                                                                                    (const T*)A, (T*)dWd));
+  DYNMO_TIMED_LAUNCH(K_FFN_DWG, st,
+                     dw_generic_kernel<T><<<dim3(th, tf, d->E), dim3(256), 0, st>>>(seg, d->F, d->H, (const T*)dG,
+                                                                                    (const T*)x_p, (T*)dWg));
+  DYNMO_TIMED_LAUNCH(K_FFN_DWU, st,
+                     dw_generic_kernel<T><<<dim3(th, tf, d->E), dim3(256), 0, st>>>(seg, d->F, d->H, (const T*)dU,
+                                                                                    (const T*)x_p, (T*)dWu));
   return DYNMO_OK;
 }
 

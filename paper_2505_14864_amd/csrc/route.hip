@@ -286,7 +286,9 @@ static int32_t launch_topk(const dynmo_desc* d, const float* logits, int32_t* ei
   const long tok_per_block = (256 / 64) * (64 / LPT);
   const long blocks = (d->T + tok_per_block - 1) / tok_per_block;
   if (blocks > 0) {
-    DYNMO_TIMED_LAUNCH(K_ROUTE_TOPK, st, route_topk_kernel<LPT><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(logits, ei, gw, d->T, d->E, d->k));
+    DYNMO_TIMED_LAUNCH(K_ROUTE_TOPK, st,
+                       route_topk_kernel<LPT><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(logits, ei, gw, d->T, d->E,
+                                                                                            d->k));
   }
   return DYNMO_OK;
 }
@@ -360,8 +362,10 @@ extern "C" int32_t dynmo_route_capacity(const dynmo_desc* d, const float* scores
   if (!scores || !expert_idx || !gate_w) return DYNMO_EINVAL;
   if (d->E != 1 || d->k != 1 || B < 0 || S <= 0 || (int64_t)B * S != d->T || cap < 0 || cap > S) return DYNMO_EINVAL;
   if (B > 0) {
-    DYNMO_TIMED_LAUNCH(K_ROUTE_CAPACITY, (hipStream_t)stream, route_capacity_kernel<<<dim3((unsigned)B), dim3(kCapThreads), 0, (hipStream_t)stream>>>(scores, expert_idx, gate_w, S,
-                                                                                            cap));
+    hipStream_t st = (hipStream_t)stream;
+    DYNMO_TIMED_LAUNCH(K_ROUTE_CAPACITY, st,
+                       route_capacity_kernel<<<dim3((unsigned)B), dim3(kCapThreads), 0, st>>>(scores, expert_idx, gate_w,
+                                                                                              S, cap));
   }
   return DYNMO_OK;
 }
@@ -373,8 +377,10 @@ extern "C" int32_t dynmo_route_active(const dynmo_desc* d, const int32_t* exit_l
   if (!exit_layer || !expert_idx || !gate_w) return DYNMO_EINVAL;
   if (d->E != 1 || d->k != 1) return DYNMO_EINVAL;
   if (d->T > 0) {
-    DYNMO_TIMED_LAUNCH(K_ROUTE_ACTIVE, (hipStream_t)stream, route_active_kernel<<<dim3((d->T + 255) / 256), dim3(256), 0, (hipStream_t)stream>>>(exit_layer, layer, expert_idx,
-                                                                                         gate_w, d->T));
+    hipStream_t st = (hipStream_t)stream;
+    DYNMO_TIMED_LAUNCH(K_ROUTE_ACTIVE, st,
+                       route_active_kernel<<<dim3((d->T + 255) / 256), dim3(256), 0, st>>>(exit_layer, layer, expert_idx,
+                                                                                           gate_w, d->T));
   }
   return DYNMO_OK;
 }
@@ -385,8 +391,10 @@ extern "C" int32_t dynmo_route_topk_bwd(const dynmo_desc* d, const float* dgate,
   if (rc) return rc;
   if (!dgate || !gate_w || !expert_idx || !dlogits) return DYNMO_EINVAL;
   if (d->T > 0) {
-    DYNMO_TIMED_LAUNCH(K_ROUTE_TOPK_BWD, (hipStream_t)stream, route_topk_bwd_kernel<<<dim3((d->T + 255) / 256), dim3(256), 0, (hipStream_t)stream>>>(dgate, gate_w, expert_idx,
-                                                                                           dlogits, d->T, d->E, d->k));
+    hipStream_t st = (hipStream_t)stream;
+    DYNMO_TIMED_LAUNCH(K_ROUTE_TOPK_BWD, st,
+                       route_topk_bwd_kernel<<<dim3((d->T + 255) / 256), dim3(256), 0, st>>>(dgate, gate_w, expert_idx,
+                                                                                             dlogits, d->T, d->E, d->k));
   }
   return DYNMO_OK;
 }
@@ -398,8 +406,10 @@ extern "C" int32_t dynmo_route_capacity_bwd(const dynmo_desc* d, const float* dg
   if (!dgate || !scores || !expert_idx || !dscores) return DYNMO_EINVAL;
   if (d->E != 1 || d->k != 1) return DYNMO_EINVAL;
   if (d->T > 0) {
-    DYNMO_TIMED_LAUNCH(K_ROUTE_CAPACITY_BWD, (hipStream_t)stream, route_capacity_bwd_kernel<<<dim3((d->T + 255) / 256), dim3(256), 0, (hipStream_t)stream>>>(dgate, scores, expert_idx,
-                                                                                               dscores, d->T));
+    hipStream_t st = (hipStream_t)stream;
+    DYNMO_TIMED_LAUNCH(K_ROUTE_CAPACITY_BWD, st,
+                       route_capacity_bwd_kernel<<<dim3((d->T + 255) / 256), dim3(256), 0, st>>>(dgate, scores, expert_idx,
+                                                                                                 dscores, d->T));
   }
   return DYNMO_OK;
 }
