@@ -662,13 +662,19 @@ size_t ffn_mfma_scratch_bytes() { return kMaxPersistent * kPartialFloats * 4 + k
 
 // Workgroups are persistent: one per compute unit (the LDS and register use allow
 // no more), capped by the number of tiles the shapes can produce.
+constexpr int kMaxDevices = 64;
+
+static int current_device() {
+  int dev = 0;
+  return hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices ? dev : 0;
+}
+
 static int persistent_blocks(int max_tiles) {
-  static int cus = 0;
+  static int cus_of[kMaxDevices] = {};  // per device, filled on first use
+  int& cus = cus_of[current_device()];
   if (cus == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-        n <= 0)
-      n = 256;
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, current_device()) != hipSuccess || n <= 0) n = 256;
     cus = n / kXcds * kXcds;
     if (cus < kXcds) cus = kXcds;
     if (cus > kMaxPersistent) cus = kMaxPersistent;
@@ -679,11 +685,12 @@ static int persistent_blocks(int max_tiles) {
 
 template <int MODE>
 static int32_t launch_mfma(const GemmParams& p, int max_tiles, KernelId id, hipStream_t st) {
-  static bool attr_set = false;
-  if (!attr_set) {
+  static bool attr_set[kMaxDevices] = {};  // the LDS size is a per-device function attribute
+  bool& done = attr_set[current_device()];
+  if (!done) {
     DYNMO_HIP_TRY(hipFuncSetAttribute((const void*)ffn_mfma_kernel<MODE>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                       kLdsBytes + kTableBytes));
-    attr_set = true;
+    done = true;
   }
   if (max_tiles <= 0) return DYNMO_OK;
   // a product that may split k always brings every compute unit: few tiles is when it splits
