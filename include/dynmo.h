@@ -162,7 +162,8 @@ int32_t dynmo_grouped_ffn_fwd(const dynmo_desc* d, const void* x_p, const int32_
  * x[src_slot[p] / k] (R^-1(e) of Sec. 2.1 applied inside the kernel's loads), so a
  * forward-only caller can skip the row copy of dynmo_permute (x_p = NULL there).
  * x [T,H], src_slot [T*k] as written by dynmo_permute; everything else, and the
- * workspace size, as for dynmo_grouped_ffn_fwd. */
+ * workspace size, as for dynmo_grouped_ffn_fwd.  x must be smaller than 2 GiB
+ * (DYNMO_EUNSUPPORTED otherwise). */
 int32_t dynmo_grouped_ffn_fwd_gather(const dynmo_desc* d, const void* x, const int32_t* src_slot,
                                      const int32_t* seg_offsets, const void* Wg, const void* Wu, const void* Wd,
                                      void* y_p, void* G_save, void* U_save, void* workspace, size_t workspace_bytes,

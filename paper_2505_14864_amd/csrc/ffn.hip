@@ -55,6 +55,9 @@ extern "C" int32_t dynmo_grouped_ffn_fwd_gather(const dynmo_desc* d, const void*
                                                 const void* Wd, void* y_p, void* G_save, void* U_save,
                                                 void* workspace, size_t workspace_bytes, void* stream) {
   if (!src_slot) return DYNMO_EINVAL;
+  // gathered rows are addressed with 32-bit byte offsets from the first row of x, whose top
+  // bit marks "outside": the whole input must stay below 2 GiB
+  if (d && (int64_t)d->T * d->H * (int64_t)elem_bytes(d->dtype) >= ((int64_t)1 << 31)) return DYNMO_EUNSUPPORTED;
   return ffn_fwd_entry(d, x, src_slot, seg_offsets, Wg, Wu, Wd, y_p, G_save, U_save, workspace, workspace_bytes,
                        stream);
 }

@@ -707,11 +707,8 @@ static int32_t launch_mfma(const GemmParams& p, int max_tiles, KernelId id, hipS
 }
 
 bool ffn_mfma_supported(const dynmo_desc* d) {
-  // piece offsets are 32-bit with the top bit as the "outside" marker: a whole operand's
-  // rows (the gathered input) and a tile's rows must stay below 2 GiB
   return d->dtype == DYNMO_BF16 && d->H % 8 == 0 && d->F % 8 == 0 &&
-         (int64_t)max_m_tiles(d, BM) * ((d->F + 127) / 128) < (1 << 30) &&
-         (int64_t)d->T * d->H * 2 < ((int64_t)1 << 31);
+         (int64_t)max_m_tiles(d, BM) * ((d->F + 127) / 128) < (1 << 30);
 }
 
 int32_t ffn_fwd_mfma(const dynmo_desc* d, const void* x_p, const int32_t* gather, const int32_t* seg, const void* Wg,

@@ -62,6 +62,9 @@ def test_bad_arguments_are_rejected_without_a_gpu():
     assert lib.dynmo_route_drop(B.C.byref(d), None, 4, None, None, 0, None) == -1
     assert lib.dynmo_grouped_ffn_fwd_gather(B.C.byref(d), None, None, None, None, None, None, None, None, None, None, 0,
                                             None) == -1
+    big = B.make_desc(300000, 4096, 512, 8, 2, "bf16")  # x is 2.4 GB: beyond the gather call's 32-bit row offsets
+    assert lib.dynmo_grouped_ffn_fwd_gather(B.C.byref(big), None, 16, None, None, None, None, None, None, None, None, 0,
+                                            None) == -2
     assert lib.dynmo_peak_copy(None, None, 16, None) == -1
     assert lib.dynmo_peak_mfma_bf16(0, None, None, None, None) == -1
     assert lib.dynmo_route_drop_workspace_bytes(B.C.byref(d)) > lib.dynmo_permute_workspace_bytes(B.C.byref(d))
