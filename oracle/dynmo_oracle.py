@@ -26,11 +26,14 @@ closed forms for the gates, an independent permutation checker, the dense
 masked FFN equivalent evaluated and differentiated by torch (fp64 autograd),
 central finite differences, special cases (E=1,k=1 dense MLP; Wd=0; nobody
 exits / everybody exits), brute-force enumeration of contiguous splits for the
-partitioner, and hand-worked imbalance vectors under tests/golden/.
+partitioner, hand-worked imbalance vectors, partitions, diffusion runs and a
+re-pack trace under tests/golden/ and in the tests, the closed form of the
+diffusion potential over order statistics, scipy's softmax and torch autograd
+for the routing variants, and a planted-mistake test that the pins catch.
 
-parity unpinned: the paper prints no tensor values for this path, so every
-value pin is one of the mathematical checks above, never a number from the
-paper.
+Every function here has at least one such pin; none is unpinned.  The paper
+prints no tensor values for this path, so no pin is a number taken from the
+paper: they are all mathematical checks of the kinds listed above.
 """
 from __future__ import annotations
 
