@@ -31,7 +31,10 @@ re-pack trace under tests/golden/ and in the tests, the closed form of the
 diffusion potential over order statistics, scipy's softmax and torch autograd
 for the routing variants, and a planted-mistake test that the pins catch.
 
-Every function here has at least one such pin; none is unpinned.  The paper
+Every function here has at least one such pin; none is unpinned.  The layer's
+component functions (permute, grouped FFN, combine and their backward passes)
+are pinned through the whole-layer chains, and the planted-mistake test shows
+that a mistake in any single one of them fails those pins.  The paper
 prints no tensor values for this path, so no pin is a number taken from the
 paper: they are all mathematical checks of the kinds listed above.
 """
