@@ -134,7 +134,7 @@ def main():
         return rows, per_task
 
     if a.reroute > 0:
-        print(json.dumps(reroute(a, w, dev, layers, step, stage_split)))
+        print(json.dumps(reroute(a, w, dev, layers, Ws, step, stage_split)))
         return
     if a.protocol:
         res = protocol(a, w, inp, dev, layers, Ws, step)
@@ -245,7 +245,7 @@ def main():
     print(json.dumps(out))
 
 
-def reroute(a, w, dev, layers, step, S):
+def reroute(a, w, dev, layers, Ws, step, S):
     """Sec. 3.3 / Sec. 4: for MoE and MoD the load changes with every routing decision, so
     the balancer runs every iteration.  Each iteration draws new router inputs on the
     device, runs the whole path, exports the loads and rebalances them on the host with
@@ -264,6 +264,7 @@ def reroute(a, w, dev, layers, step, S):
     rec = {"uniform": [], "partition": [], "diffusion": [], "diffusion_rounds": []}
     t_step, t_bal = [], []
     prev = None
+    by_time = {"split_by_param": [], "split_by_time": []} if len(layers) > 1 else None
     for it in range(a.reroute):
         # the routing decision of this iteration (drifting preference: the bias rotates over the experts)
         if w.mode == "moe":
@@ -290,12 +291,37 @@ def reroute(a, w, dev, layers, step, S):
         rec["diffusion_rounds"].append(rounds)
         t_step.append(t1 - t0)
         t_bal.append(t2 - t1)
+        if by_time is not None:
+            # The profiling step (Sec. 3.1, Sec. 5 "by Time"): time each layer's forward and backward with
+            # events, balance once on the parameter/flop loads and once on the measured times, and judge
+            # both splits by the measured stage times.
+            L = len(layers)
+            ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(L)]
+            x = dev["x"]
+            for i, layer in enumerate(layers):
+                layer.route_active(dev["exit_layer"], i + 1)
+                ev[i][0].record()
+                x = layer.forward(x, *Ws[i])
+                ev[i][1].record()
+            g = dev["dout"]
+            for i in range(L - 1, -1, -1):
+                ev[i][2].record()
+                g = layers[i].backward(g, *Ws[i])
+                ev[i][3].record()
+            torch.cuda.synchronize()
+            times = [ev[i][0].elapsed_time(ev[i][1]) + ev[i][2].elapsed_time(ev[i][3]) for i in range(L)]
+            tb, _ = B.dynmo_partition(times, S)
+            by_time["split_by_param"].append(round(B.dynmo_imbalance(B.dynmo_stage_loads(times, pb)), 4))
+            by_time["split_by_time"].append(round(B.dynmo_imbalance(B.dynmo_stage_loads(times, tb)), 4))
     n = max(1, len(t_step))
     mean = lambda xs: sum(xs) / max(1, len(xs))
     return {"workload": "config %d: %s" % (a.config, w.name), "iterations": a.reroute, "stages": S,
             "tasks": "layers" if len(layers) > 1 else "experts",
             "imbalance": rec,
             "mean_imbalance": {k: round(mean(v), 4) for k, v in rec.items() if k != "diffusion_rounds"},
+            "imbalance_of_measured_stage_times": by_time,
+            "mean_imbalance_of_measured_stage_times": (
+                {k: round(mean(v), 4) for k, v in by_time.items()} if by_time else None),
             "ms_per_iteration": round(1e3 * sum(t_step) / n, 4),
             "balancing_us_per_iteration": round(1e6 * sum(t_bal) / n, 1),
             "balancing_overhead": round(sum(t_bal) / max(1e-12, sum(t_step)), 5)}
