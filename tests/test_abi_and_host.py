@@ -219,3 +219,32 @@ def test_bench_work_model():
     R4 = w4.B * w4.cap
     assert bench.kernel_work("combine", w4, R4, w4.T)[1] == (R4 + 2 * w4.T) * w4.H * 2 + 8.0 * w4.T
     assert bench.kernel_work("route_topk", w, R, w.T) is None
+
+
+def test_product_and_oracle_do_not_import_each_other():
+    """The product path never touches the oracle (no CPU fallback), the oracle never
+    touches the product; only the seeded input generators are shared."""
+    import ast
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+    def imported(path):
+        names = set()
+        for node in ast.walk(ast.parse(open(path).read())):
+            if isinstance(node, ast.Import):
+                names.update(a.name for a in node.names)
+            elif isinstance(node, ast.ImportFrom):
+                names.add(("." * node.level) + (node.module or ""))
+                names.update("%s.%s" % (node.module or "", a.name) for a in node.names)
+        return names
+
+    pkg = os.path.join(root, "paper_2505_14864_amd")
+    for f in os.listdir(pkg):
+        if f.endswith(".py"):
+            assert not any("oracle" in n for n in imported(os.path.join(pkg, f))), f
+    for f in os.listdir(os.path.join(root, "oracle")):
+        if f.endswith(".py"):
+            assert not any("paper_2505_14864_amd" in n or "binding" in n for n in imported(os.path.join(root, "oracle", f))), f
+    # the input generators hold none of the method's arithmetic: no matmul, softmax, sort or top-k
+    src = open(os.path.join(pkg, "workloads.py")).read()
+    for word in ("matmul", "argsort", "softmax", "einsum", " @ "):
+        assert word not in src, word
