@@ -700,3 +700,25 @@ def test_layer_under_graph_capture():
         for n in names:
             a, b = (eager[n][:R], replayed[n][:R]) if n in ("y_p", "G", "U") else (eager[n], replayed[n])
             assert torch.equal(a, b), "%s differs on replay %d" % (n, trial)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_shapes(seed):
+    """Seeded random shapes (expert counts 1..64, 1..8 slots, sizes on and off the tile
+    boundaries, flat to very skewed routing) through the bf16 layer, full check."""
+    rng = np.random.default_rng(4000 + seed)
+    E = int(rng.choice([1, 2, 3, 5, 8, 16, 33, 64]))
+    k = int(rng.integers(1, min(E, 8) + 1))
+    T = int(rng.choice([1, 7, 64, 255, 256, 257, 600, 1500]))
+    H = int(rng.choice([8, 24, 64, 136, 256, 520, 1024]))
+    F = int(rng.choice([8, 40, 128, 264, 688, 1032, 2048]))
+    if T * k * (H + F) * E > 4e8:
+        T = 256
+    w = wl.scaled(wl.CONFIGS[2], T=T, H=H, F=F, E=E, k=k, seed=4100 + seed, zipf_s=float(rng.choice([0.0, 1.1, 2.5])))
+    say("random shape %d: T=%d H=%d F=%d E=%d k=%d zipf=%.1f" % (seed, T, H, F, E, k, w.zipf_s))
+    inp = wl.make_inputs(w, threads=2)
+    layer = run_moe(w, inp)
+    f = f32_inputs(inp)
+    ref = orc.moe_layer(f["logits"], f["x"], f["Wg"], f["Wu"], f["Wd"], w.k, f["dout"])
+    assert np.array_equal(to_host(layer.expert_idx), ref["expert_idx"])
+    check_layer_full(layer, ref, w.dtype)
