@@ -75,6 +75,21 @@ def kernel_work(name, w, R_total, T):
     return table.get(name)
 
 
+def measured_traffic(config, kernel):
+    """HBM bytes per launch of `kernel` from the committed counter summary of this configuration (a table whose
+    rows are: kernel, read MB, written MB, total MB, ...), or None when no summary covers it."""
+    import glob
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "hbm_traffic_config%d_*.txt" % config))):
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 4 and f[0] in (kernel, kernel + "_kernel"):
+                try:
+                    return int(round(float(f[3]) * 1e6))
+                except ValueError:
+                    pass
+    return None
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -189,10 +204,7 @@ def main():
         kernels.append(ent)
     kernels.sort(key=lambda e: -e["total_ms"])
     dom = next((e for e in kernels if "bound" in e), None)
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if dom and os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get("%s/%s" % (dom["name"], w.name))
+    traffic = measured_traffic(a.config, dom["name"]) if dom else None
     roofline = None
     if dom:
         roofline = {"kernel": dom["name"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
