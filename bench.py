@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run one plain 1 GiB device copy (a known-size reference for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--folded-combine", action="store_true",
+                    help="configurations with one slot per token (4, 5): fold the combine into the last product "
+                         "(dynmo_grouped_ffn_fwd_combine) instead of the separate dynmo_combine pass")
     ap.add_argument("--reroute", type=int, default=0, metavar="N",
                     help="instead of the headline line: N iterations with fresh router inputs each (the routing "
                          "decision changes every iteration), the exported loads rebalanced every iteration; prints "
@@ -120,6 +123,11 @@ def main():
         Ws = [(dev["Wg"], dev["Wu"], dev["Wd"])]
     stage_split = 2 if L > 1 else min(4, w.E)
 
+    if a.folded_combine and w.k != 1:
+        print("bench.py: --folded-combine needs a configuration with one slot per token (4 or 5)", file=sys.stderr)
+        sys.exit(2)
+    primed = []
+
     def step():
         """One pass of the hot path; returns (routed rows, loads for the balancer)."""
         x = dev["x"]
@@ -130,7 +138,15 @@ def main():
                 layer.route_capacity(dev["scores"], w.cap)
             else:
                 layer.route_active(dev["exit_layer"], i + 1)
-            x = layer.forward(x, *Ws[i])
+            if a.folded_combine:
+                # The residual stream's rows of unrouted tokens are not rewritten.  Every step sees the same
+                # routing, so each layer's output buffer is given them once, in the first (warm-up) step.
+                if len(primed) < L:
+                    layer.out.copy_(x)
+                    primed.append(i)
+                x = layer.forward_folded(x, *Ws[i], out=layer.out)
+            else:
+                x = layer.forward(x, *Ws[i])
         g = dev["dout"]
         for i in range(L - 1, -1, -1):
             g = layers[i].backward(g, *Ws[i])
@@ -247,7 +263,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": "config %d: %s (T=%d H=%d F=%d E=%d k=%d%s)" % (
             a.config, w.name, w.T, w.H, w.F, w.E, w.k, ", %d layers" % L if L > 1 else ""),
-            "routed_rows_per_step": R_step, "tokens_per_s": round(w.T * a.steps / elapsed, 1)},
+            "routed_rows_per_step": R_step, "tokens_per_s": round(w.T * a.steps / elapsed, 1),
+            "folded_combine": bool(a.folded_combine)},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": kernels,

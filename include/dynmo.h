@@ -169,6 +169,24 @@ int32_t dynmo_grouped_ffn_fwd_gather(const dynmo_desc* d, const void* x, const i
                                      void* y_p, void* G_save, void* U_save, void* workspace, size_t workspace_bytes,
                                      void* stream);
 
+/* The same layer for k = 1 (at most one routed row per token: the Mixture-of-Depths
+ * block of Sec. 2.6, the shrinking layers of Sec. 2.5, top-1 MoE) with the weighted
+ * combine folded into the stores of the last product: for every routed row p, with
+ * t = src_slot[p],  out[t] = res[t] + gate_w[t] * Y[p]  (fp32 sum, rounded once).
+ * Rows of out whose token has no routed row are NOT written: with res == out the
+ * residual stream is updated in place and unrouted tokens pass through at no traffic;
+ * with res == NULL (zero) or a separate res the caller owns those rows.
+ * Exactly one of x_p [T,H] (expert-sorted rows) and x [T,H] (token order, rows fetched
+ * through src_slot as in dynmo_grouped_ffn_fwd_gather, same 2 GiB limit) is non-NULL;
+ * x may be out (the first product has finished reading before the last one stores).
+ * gate_w [T] fp32; res, out [T,H]; y_p [T,H] or NULL (the unweighted rows, which
+ * dynmo_combine_bwd needs for the gate gradient); G_save, U_save, workspace as for
+ * dynmo_grouped_ffn_fwd.  d->k != 1 gives DYNMO_EINVAL. */
+int32_t dynmo_grouped_ffn_fwd_combine(const dynmo_desc* d, const void* x_p, const void* x, const int32_t* src_slot,
+                                      const int32_t* seg_offsets, const void* Wg, const void* Wu, const void* Wd,
+                                      const float* gate_w, const void* res, void* out, void* y_p, void* G_save,
+                                      void* U_save, void* workspace, size_t workspace_bytes, void* stream);
+
 size_t dynmo_grouped_ffn_bwd_workspace_bytes(const dynmo_desc* d);
 
 /* Backward of dynmo_grouped_ffn_fwd: dA = dY Wd; dG = dA U silu'(G); dU = dA silu(G);

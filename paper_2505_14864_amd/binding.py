@@ -56,6 +56,7 @@ SIGNATURES = {
     "dynmo_grouped_ffn_fwd_workspace_bytes": (C.c_size_t, [_D]),
     "dynmo_grouped_ffn_fwd": (_I, [_D, _P, _P, _P, _P, _P, _P, _P, _P, _P, C.c_size_t, _P]),
     "dynmo_grouped_ffn_fwd_gather": (_I, [_D, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, C.c_size_t, _P]),
+    "dynmo_grouped_ffn_fwd_combine": (_I, [_D] + [_P] * 14 + [C.c_size_t, _P]),
     "dynmo_grouped_ffn_bwd_workspace_bytes": (C.c_size_t, [_D]),
     "dynmo_grouped_ffn_bwd": (_I, [_D] + [_P] * 13 + [C.c_size_t, _P]),
     "dynmo_combine": (_I, [_D, _P, _P, _P, _P, _P, _P]),
@@ -200,6 +201,14 @@ def dynmo_grouped_ffn_fwd_gather(d, x, src_slot, seg_offsets, Wg, Wu, Wd, y_p, G
     _check("dynmo_grouped_ffn_fwd_gather", lib().dynmo_grouped_ffn_fwd_gather(
         C.byref(d), _ptr(x), _ptr(src_slot), _ptr(seg_offsets), _ptr(Wg), _ptr(Wu), _ptr(Wd), _ptr(y_p),
         _ptr(G_save), _ptr(U_save), _ptr(workspace), workspace.numel(), _stream(stream)))
+
+
+def dynmo_grouped_ffn_fwd_combine(d, x_p, x, src_slot, seg_offsets, Wg, Wu, Wd, gate_w, res, out, y_p, G_save, U_save,
+                                  workspace, stream=None):
+    _check("dynmo_grouped_ffn_fwd_combine", lib().dynmo_grouped_ffn_fwd_combine(
+        C.byref(d), _ptr(x_p), _ptr(x), _ptr(src_slot), _ptr(seg_offsets), _ptr(Wg), _ptr(Wu), _ptr(Wd), _ptr(gate_w),
+        _ptr(res), _ptr(out), _ptr(y_p), _ptr(G_save), _ptr(U_save), _ptr(workspace), workspace.numel(),
+        _stream(stream)))
 
 
 def dynmo_grouped_ffn_bwd_workspace_bytes(d):

@@ -46,10 +46,21 @@ __device__ __forceinline__ void swiglu_bwd(float dA, float g, float u, float* a,
   *du = dA * gs;
 }
 
+// The combine of a one-slot layer (k = 1) folded into the stores of Y = A Wd^T: row p also
+// goes to out[t] = res[t] + scale[t] * Y[p], t = scatter[p].  res may be nullptr (zero) or out.
+struct FoldedCombine {
+  const int32_t* scatter;
+  const float* scale;
+  const void* res;
+  void* out;
+};
+
 // In both forward families `gather` is NULL (x_p holds the expert-sorted rows) or the
 // slot index: row p is then x_p[gather[p] / k], x_p being the token-ordered input.
+// `fc` is NULL or the folded combine; y_p may be NULL only with it.
 int32_t ffn_fwd_generic(const dynmo_desc* d, const void* x_p, const int32_t* gather, const int32_t* seg, const void* Wg,
-                        const void* Wu, const void* Wd, void* y_p, void* G, void* U, void* A, hipStream_t st);
+                        const void* Wu, const void* Wd, void* y_p, void* G, void* U, void* A, const FoldedCombine* fc,
+                        hipStream_t st);
 int32_t ffn_bwd_generic(const dynmo_desc* d, const void* dy_p, const void* x_p, const void* G, const void* U,
                         const int32_t* seg, const void* Wg, const void* Wu, const void* Wd, void* dx_p, void* dWg,
                         void* dWu, void* dWd, void* dG, void* dU, void* A, hipStream_t st);
@@ -60,7 +71,7 @@ bool ffn_mfma_supported(const dynmo_desc* d);
 size_t ffn_mfma_scratch_bytes();  // 256-byte aligned device scratch both calls below need
 int32_t ffn_fwd_mfma(const dynmo_desc* d, const void* x_p, const int32_t* gather, const int32_t* seg, const void* Wg,
                      const void* Wu, const void* Wd, void* y_p, void* G, void* U, void* A, void* scratch,
-                     hipStream_t st);
+                     const FoldedCombine* fc, hipStream_t st);
 int32_t ffn_bwd_mfma(const dynmo_desc* d, const void* dy_p, const void* x_p, const void* G, const void* U,
                      const int32_t* seg, const void* Wg, const void* Wu, const void* Wd, void* dx_p, void* dWg,
                      void* dWu, void* dWd, void* dG, void* dU, void* A, void* scratch, hipStream_t st);

@@ -29,17 +29,18 @@ extern "C" size_t dynmo_grouped_ffn_bwd_workspace_bytes(const dynmo_desc* d) {
 namespace dynmo {
 static int32_t ffn_fwd_entry(const dynmo_desc* d, const void* rows, const int32_t* gather, const int32_t* seg_offsets,
                              const void* Wg, const void* Wu, const void* Wd, void* y_p, void* G_save, void* U_save,
-                             void* workspace, size_t workspace_bytes, void* stream) {
+                             void* workspace, size_t workspace_bytes, const FoldedCombine* fc, void* stream) {
   int32_t rc = check_desc(d);
   if (rc) return rc;
-  if (!rows || !seg_offsets || !Wg || !Wu || !Wd || !y_p || !G_save || !U_save || !workspace) return DYNMO_EINVAL;
+  if (!rows || !seg_offsets || !Wg || !Wu || !Wd || !G_save || !U_save || !workspace) return DYNMO_EINVAL;
+  if (!y_p && !fc) return DYNMO_EINVAL;
   if (workspace_bytes < dynmo_grouped_ffn_fwd_workspace_bytes(d)) return DYNMO_EWORKSPACE;
   if (max_m_tiles(d, 64) > 65535) return DYNMO_EUNSUPPORTED;
   void* A = (void*)align_up((size_t)workspace, 256);
   if (ffn_mfma_supported(d))
     return ffn_fwd_mfma(d, rows, gather, seg_offsets, Wg, Wu, Wd, y_p, G_save, U_save, A, (char*)A + act_bytes(d),
-                        (hipStream_t)stream);
-  return ffn_fwd_generic(d, rows, gather, seg_offsets, Wg, Wu, Wd, y_p, G_save, U_save, A, (hipStream_t)stream);
+                        fc, (hipStream_t)stream);
+  return ffn_fwd_generic(d, rows, gather, seg_offsets, Wg, Wu, Wd, y_p, G_save, U_save, A, fc, (hipStream_t)stream);
 }
 }  // namespace dynmo
 
@@ -47,7 +48,7 @@ extern "C" int32_t dynmo_grouped_ffn_fwd(const dynmo_desc* d, const void* x_p, c
                                          const void* Wg, const void* Wu, const void* Wd, void* y_p, void* G_save,
                                          void* U_save, void* workspace, size_t workspace_bytes, void* stream) {
   return ffn_fwd_entry(d, x_p, nullptr, seg_offsets, Wg, Wu, Wd, y_p, G_save, U_save, workspace, workspace_bytes,
-                       stream);
+                       nullptr, stream);
 }
 
 extern "C" int32_t dynmo_grouped_ffn_fwd_gather(const dynmo_desc* d, const void* x, const int32_t* src_slot,
@@ -59,7 +60,20 @@ extern "C" int32_t dynmo_grouped_ffn_fwd_gather(const dynmo_desc* d, const void*
   // bit marks "outside": the whole input must stay below 2 GiB
   if (d && (int64_t)d->T * d->H * (int64_t)elem_bytes(d->dtype) >= ((int64_t)1 << 31)) return DYNMO_EUNSUPPORTED;
   return ffn_fwd_entry(d, x, src_slot, seg_offsets, Wg, Wu, Wd, y_p, G_save, U_save, workspace, workspace_bytes,
-                       stream);
+                       nullptr, stream);
+}
+
+extern "C" int32_t dynmo_grouped_ffn_fwd_combine(const dynmo_desc* d, const void* x_p, const void* x,
+                                                 const int32_t* src_slot, const int32_t* seg_offsets, const void* Wg,
+                                                 const void* Wu, const void* Wd, const float* gate_w, const void* res,
+                                                 void* out, void* y_p, void* G_save, void* U_save, void* workspace,
+                                                 size_t workspace_bytes, void* stream) {
+  if (!d || !src_slot || !gate_w || !out || (x_p == nullptr) == (x == nullptr)) return DYNMO_EINVAL;
+  if (d->k != 1) return DYNMO_EINVAL;  // with two slots per token two rows would meet in one output row
+  if (x && (int64_t)d->T * d->H * (int64_t)elem_bytes(d->dtype) >= ((int64_t)1 << 31)) return DYNMO_EUNSUPPORTED;
+  const FoldedCombine fc = {src_slot, gate_w, res, out};
+  return ffn_fwd_entry(d, x_p ? x_p : x, x_p ? nullptr : src_slot, seg_offsets, Wg, Wu, Wd, y_p, G_save, U_save,
+                       workspace, workspace_bytes, &fc, stream);
 }
 
 extern "C" int32_t dynmo_grouped_ffn_bwd(const dynmo_desc* d, const void* dy_p, const void* x_p, const void* G_save,

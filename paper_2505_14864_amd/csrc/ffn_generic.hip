@@ -115,7 +115,9 @@ __global__ __launch_bounds__(256) void seg_gemm_generic_kernel(const int32_t* __
                                                                const T* __restrict__ A2, const T* __restrict__ B2, long a_rs,
                                                                long b_es, long b_rs, long b_ks, T* __restrict__ C,
                                                                const T* __restrict__ Gs, const T* __restrict__ Us,
-                                                               T* __restrict__ dG, T* __restrict__ dU, T* __restrict__ Aout) {
+                                                               T* __restrict__ dG, T* __restrict__ dU, T* __restrict__ Aout,
+                                                               const int32_t* __restrict__ scatter,
+                                                               const float* __restrict__ scale, const T* res, T* out) {
   __shared__ float As[GK][GT + 1], Bs[GK][GT + 1];
   int e, m0, m_end;
   if (!find_m_tile(seg, E, blockIdx.y, GT, &e, &m0, &m_end)) return;
@@ -134,7 +136,12 @@ __global__ __launch_bounds__(256) void seg_gemm_generic_kernel(const int32_t* __
       if (n >= N) continue;
       const long o = (long)m * N + n;
       if (EPI == EPI_STORE) {
-        Elem<T>::store(C + o, acc[i][j]);
+        if (C) Elem<T>::store(C + o, acc[i][j]);
+        if (scatter) {  // folded combine of a one-slot layer
+          const int token = scatter[m];
+          const long ot = (long)token * N + n;
+          Elem<T>::store(out + ot, (res ? Elem<T>::load(res + ot) : 0.f) + scale[token] * acc[i][j]);
+        }
       } else {
         const float g = Elem<T>::load(Gs + o), u = Elem<T>::load(Us + o);
         float a, dg, du;
@@ -175,7 +182,7 @@ __global__ __launch_bounds__(256) void dw_generic_kernel(const int32_t* __restri
 template <typename T>
 static int32_t fwd_generic_t(const dynmo_desc* d, const void* x_p, const int32_t* gather, const int32_t* seg,
                              const void* Wg, const void* Wu, const void* Wd, void* y_p, void* G, void* U, void* A,
-                             hipStream_t st) {
+                             const FoldedCombine* fc, hipStream_t st) {
   const int m_tiles = max_m_tiles(d, GT);
   if (m_tiles == 0) return DYNMO_OK;
   const long FH = (long)d->F * d->H;
@@ -184,7 +191,8 @@ static int32_t fwd_generic_t(const dynmo_desc* d, const void* x_p, const int32_t
   // Y = A Wd^T : B(n=h, k=f) = Wd[e][h*F + f]
   DYNMO_TIMED_LAUNCH(K_FFN_DOWN, st, seg_gemm_generic_kernel<T, EPI_STORE><<<dim3((d->H + GT - 1) / GT, m_tiles), dim3(256), 0, st>>>(
       seg, d->E, d->H, d->F, (const T*)A, (const T*)Wd, nullptr, nullptr, d->F, FH, d->F, 1, (T*)y_p, nullptr, nullptr,
-      nullptr, nullptr, nullptr));
+      nullptr, nullptr, nullptr, fc ? fc->scatter : nullptr, fc ? fc->scale : nullptr, fc ? (const T*)fc->res : nullptr,
+      fc ? (T*)fc->out : nullptr));
   return DYNMO_OK;
 }
 
@@ -199,11 +207,11 @@ static int32_t bwd_generic_t(const dynmo_desc* d, const void* dy_p, const void* 
     // dA = dY Wd : B(n=f, k=h) = Wd[e][h*F + f]; epilogue gives A, dG, dU
     DYNMO_TIMED_LAUNCH(K_FFN_DA, st, seg_gemm_generic_kernel<T, EPI_SWIGLU_BWD><<<dim3(tf, m_tiles), dim3(256), 0, st>>>(
         seg, d->E, d->F, d->H, (const T*)dy_p, (const T*)Wd, nullptr, nullptr, d->H, FH, 1, d->F, nullptr, (const T*)G,
-        (const T*)U, (T*)dG, (T*)dU, (T*)A));
+        (const T*)U, (T*)dG, (T*)dU, (T*)A, nullptr, nullptr, nullptr, nullptr));
     // dX = dG Wg + dU Wu : B(n=h, k=f) = W[e][f*H + h]
     DYNMO_TIMED_LAUNCH(K_FFN_DX, st, seg_gemm_generic_kernel<T, EPI_STORE><<<dim3(th, m_tiles), dim3(256), 0, st>>>(
         seg, d->E, d->H, d->F, (const T*)dG, (const T*)Wg, (const T*)dU, (const T*)Wu, d->F, FH, 1, d->H, (T*)dx_p, nullptr,
-        nullptr, nullptr, nullptr, nullptr));
+        nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr));
   }
   // The weight gradients are written for every expert, rows or not.
   DYNMO_TIMED_LAUNCH(K_FFN_DWD, st,
@@ -219,9 +227,10 @@ static int32_t bwd_generic_t(const dynmo_desc* d, const void* dy_p, const void* 
 }
 
 int32_t ffn_fwd_generic(const dynmo_desc* d, const void* x_p, const int32_t* gather, const int32_t* seg, const void* Wg,
-                        const void* Wu, const void* Wd, void* y_p, void* G, void* U, void* A, hipStream_t st) {
-  return d->dtype == DYNMO_BF16 ? fwd_generic_t<bf16_t>(d, x_p, gather, seg, Wg, Wu, Wd, y_p, G, U, A, st)
-                                : fwd_generic_t<float>(d, x_p, gather, seg, Wg, Wu, Wd, y_p, G, U, A, st);
+                        const void* Wu, const void* Wd, void* y_p, void* G, void* U, void* A, const FoldedCombine* fc,
+                        hipStream_t st) {
+  return d->dtype == DYNMO_BF16 ? fwd_generic_t<bf16_t>(d, x_p, gather, seg, Wg, Wu, Wd, y_p, G, U, A, fc, st)
+                                : fwd_generic_t<float>(d, x_p, gather, seg, Wg, Wu, Wd, y_p, G, U, A, fc, st);
 }
 
 int32_t ffn_bwd_generic(const dynmo_desc* d, const void* dy_p, const void* x_p, const void* G, const void* U,

@@ -3,6 +3,7 @@
 // One kernel template covers the five products of the layer:
 //   GATEUP  G = X Wg^T, U = X Wu^T, A = silu(G) U      (A, B both K-contiguous)
 //   DOWN    Y = A Wd^T                                  (A, B both K-contiguous)
+//           (DOWN_FOLD: also out[t] = res[t] + w[t] Y[p], the combine of a one-slot layer)
 //   DA      dA = dY Wd  -> A, dG, dU                    (B stored [K][N])
 //   DX      dX = dG Wg + dU Wu                          (B stored [K][N], two K phases)
 //   DW      dW[e] = P_e^T Q_e over the rows of expert e (A, B both stored [K][M/N])
@@ -61,7 +62,8 @@ constexpr int kSplitHdrInts = 4 + 4 * kMaxSplitTiles;  // {split, patches, slots
 static_assert(256 * kPitchK == 64 * kPitchT, "both tile layouts must have the same size");
 static_assert((kMfmaThreads / 64) * kEpWaveBytes <= kLdsBytes, "epilogue patches must fit in the staging buffers");
 
-enum { MODE_GATEUP = 0, MODE_DOWN = 1, MODE_DA = 2, MODE_DX = 3, MODE_DW = 4 };
+// MODE_DOWN_FOLD is MODE_DOWN with the weighted combine of a one-slot layer in its stores
+enum { MODE_GATEUP = 0, MODE_DOWN = 1, MODE_DA = 2, MODE_DX = 3, MODE_DW = 4, MODE_DOWN_FOLD = 5 };
 
 struct GemmParams {
   const int32_t* seg;
@@ -85,6 +87,12 @@ struct GemmParams {
   float* partial;     // kMaxPersistent fp32 partial tiles, then kSplitHdrInts ints (modes that may split k)
   const int32_t* gather;  // MODE_GATEUP: row p of operand A is row gather[p] / gather_div of A1, or nullptr
   int gather_div;
+  // MODE_DOWN_FOLD (k = 1): row p also goes to row t = scatter[p] of out as
+  // res[t] + scale[t] * value (res nullptr = 0; res may be out); C0 may then be nullptr
+  const int32_t* scatter;
+  const float* scale;
+  const bf16_t* res;
+  bf16_t* out;
 };
 
 // ---- global -> registers -> LDS staging ---------------------------------------
@@ -104,6 +112,15 @@ __device__ __forceinline__ u32x4 bload(rsrc_t rs, uint32_t off) {
   return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0));
 }
 
+// The thread index behind a compiler barrier.  Offsets derived from it are recomputed where
+// they are used (once per output tile) instead of being computed at kernel entry and kept
+// in scratch memory across the k loop, whose own registers fill the whole file.
+__device__ __forceinline__ int tid_now() {
+  int t = threadIdx.x;
+  asm volatile("" : "+v"(t));
+  return t;
+}
+
 // Per-thread offsets of the eight pieces of a staged tile.  Row validity does not
 // change along k, so it is folded into the offsets once per output tile; the k
 // validity is applied per k tile (it only bites in a ragged last tile).
@@ -116,7 +133,7 @@ struct Pieces {
 // `wrap` = 128 for the gate/up pairing (pieces 4..7 repeat rows 0..127 of a second matrix).
 __device__ __forceinline__ Pieces pieces_rowk(uint32_t ld_bytes, int rows_left, int wrap) {
   Pieces ps;
-  const int tid = threadIdx.x;
+  const int tid = tid_now();
   const int r0 = tid >> 3, kc = (tid & 7) * 8;
 #pragma unroll
   for (int j = 0; j < kPieces; ++j) {
@@ -130,7 +147,7 @@ __device__ __forceinline__ Pieces pieces_rowk(uint32_t ld_bytes, int rows_left, 
 // [k][row] memory: piece j of a thread is k-row tid/32 + 16 j, row offset (tid%32)*8
 __device__ __forceinline__ Pieces pieces_krow(uint32_t ld_bytes, int rows_left) {
   Pieces ps;
-  const int tid = threadIdx.x;
+  const int tid = tid_now();
   const int k0 = tid >> 5, rc = (tid & 31) * 8;
 #pragma unroll
   for (int j = 0; j < kPieces; ++j) {
@@ -159,7 +176,7 @@ __device__ __forceinline__ void store_piece(char* tile, const u32x4& v, int j) {
 __device__ __forceinline__ Pieces pieces_rowk_gather(uint32_t ld_bytes, int row0, int rows_left,
                                                      const int32_t* __restrict__ rowmap, int rowdiv) {
   Pieces ps;
-  const int tid = threadIdx.x;
+  const int tid = tid_now();
   const int r0 = tid >> 3, kc = (tid & 7) * 8;
 #pragma unroll
   for (int j = 0; j < kPieces; ++j) {
@@ -330,7 +347,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   // at once, every one on its own chunk of the k range: a patch keeps the operand
   // sharing of an ordinary round.  The chunks leave fp32 partial tiles in global memory,
   // which a second small kernel adds up in chunk order and converts.
-  constexpr bool CAN_SPLIT = MODE == MODE_DOWN || MODE == MODE_DX;
+  constexpr bool CAN_SPLIT = MODE == MODE_DOWN || MODE == MODE_DOWN_FOLD || MODE == MODE_DX;
   const int slot = blockIdx.x / kXcds;
   int first = 0, mine = tb.total;  // this XCD's run of the list
   int split = 1, patches = 0, tail_tiles = 0;
@@ -536,6 +553,13 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   // (lane/32)*4 + r%4, column j*32 + lane%32 of the wavefront's 64x128 part.  Each
   // wavefront passes one 32-row band at a time through its own LDS patch (fp32,
   // padded rows) so that global memory sees 16-byte accesses along rows.
+  // The lane and wavefront indices are taken afresh behind a compiler barrier: the addresses
+  // below would otherwise be computed before the k loop and kept in scratch memory across it.
+  {
+  int lane_again = threadIdx.x & 63, wave_again = threadIdx.x >> 6;
+  asm volatile("" : "+v"(lane_again), "+v"(wave_again));
+  const int lane = lane_again, wave = wave_again;
+  const int wm = wave >> 1, wn = wave & 1;
   float* ep = (float*)(smem + wave * kEpWaveBytes);
   const bf16_t* __restrict__ Gs = p.G;
   const bf16_t* __restrict__ Us = p.U;
@@ -553,13 +577,37 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     if (i > 0) __syncthreads();
+    const int band_row = t.m0 + wm * 64 + i * 32;
+    // folded combine: the band's token indices, then (once the band's accumulators have left
+    // their registers) weights and residual rows, are requested all at once, so that their
+    // latencies overlap each other and the LDS pass (out may alias res: every element is
+    // read and written by the same thread only)
+    int token[8];
+    float weight[8];
+    u32x4 resid[8];
+    const bool fold = MODE == MODE_DOWN_FOLD && !parted;
+    if (fold) {
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        const int row = band_row + s * 4 + (lane >> 4);
+        token[s] = row < t.m_end ? p.scatter[row] : p.scatter[t.m0];
+      }
+    }
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r)
         ep[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * kEpPitch + j * 32 + (lane & 31)] = acc[i][j][r];
+    if (fold) {
+      const int col = t.n0 + wn * 128 + (lane & 15) * 8;
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        weight[s] = p.scale[token[s]];
+        resid[s] = u32x4{0u, 0u, 0u, 0u};
+        if (p.res && col < n_end) resid[s] = *(const u32x4*)(p.res + (long)token[s] * p.ldc + col);
+      }
+    }
     __syncthreads();
-    const int band_row = t.m0 + wm * 64 + i * 32;
     if (MODE == MODE_GATEUP) {
       // LDS row: 64 gate columns then the 64 matching up columns
 #pragma unroll
@@ -606,10 +654,18 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
             *(u32x4*)(C2 + o) = pack16<bf16_t>(a_);
           }
         } else if (ok) {
-          *(u32x4*)(C0 + o) = pack16<bf16_t>(v);
+          if (MODE != MODE_DOWN_FOLD || C0) *(u32x4*)(C0 + o) = pack16<bf16_t>(v);
+          if (MODE == MODE_DOWN_FOLD) {
+            float r[8];
+            unpack16<bf16_t>(resid[s], r);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) r[q] += weight[s] * v[q];
+            *(u32x4*)(p.out + (long)token[s] * p.ldc + col) = pack16<bf16_t>(r);
+          }
         }
       }
     }
+  }
   }
   __syncthreads();  // the LDS patches are reused by the next tile's staging
   }  // tile loop
@@ -620,7 +676,9 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
 // the grid covers the most tiles a split can have, and workgroups beyond what the first
 // pass recorded in the header return at once.
 __global__ __launch_bounds__(256) void ffn_split_reduce_kernel(const float* __restrict__ partial, bf16_t* __restrict__ C,
-                                                               long ldc, int N) {
+                                                               long ldc, int N, const int32_t* __restrict__ scatter,
+                                                               const float* __restrict__ scale, const bf16_t* res,
+                                                               bf16_t* out) {
   const int32_t* hdr = (const int32_t*)(partial + kMaxPersistent * kPartialFloats);
   const int split = hdr[0], slots = hdr[2], tiles = hdr[3];
   const int u = blockIdx.x >> 2, quarter = blockIdx.x & 3;
@@ -630,14 +688,31 @@ __global__ __launch_bounds__(256) void ffn_split_reduce_kernel(const float* __re
   // chunk c of split tile u was run by workgroup (u % slots) of XCD (u / slots) * split + c
   const float* src = partial + (size_t)((u % slots) * kXcds + (u / slots) * split) * kPartialFloats;
   const int col = (threadIdx.x & 63) * 4;
-#pragma unroll 2
+  const bool cols_ok = n0 + col < N;
+  // folded combine: token index and weight of each of this thread's 16 rows, requested at once
+  int token[16];
+  float weight[16];
+  if (scatter) {
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+      const int row = m0 + quarter * 64 + it * 4 + (threadIdx.x >> 6);
+      token[it] = scatter[row < m_end ? row : m0];
+    }
+#pragma unroll
+    for (int it = 0; it < 16; ++it) weight[it] = scale[token[it]];
+  }
+#pragma unroll
   for (int it = 0; it < 16; ++it) {
     const int rl = quarter * 64 + it * 4 + (threadIdx.x >> 6);
+    const int row = m0 + rl;
+    const bool ok = row < m_end && cols_ok;
     // all chunks' loads are issued before the first add; the sum runs in chunk order
     float4 v[kXcds];
 #pragma unroll
     for (int c = 0; c < kXcds; ++c)
       if (c < split) v[c] = *(const float4*)(src + (size_t)c * kPartialFloats + rl * BN + col);
+    uint2 q = make_uint2(0u, 0u);
+    if (scatter && res && ok) q = *(const uint2*)(res + (long)token[it] * ldc + n0 + col);
     float4 sum = v[0];
 #pragma unroll
     for (int c = 1; c < kXcds; ++c)
@@ -647,12 +722,19 @@ __global__ __launch_bounds__(256) void ffn_split_reduce_kernel(const float* __re
         sum.z += v[c].z;
         sum.w += v[c].w;
       }
-    const int row = m0 + rl;
-    if (row < m_end && n0 + col < N) {
+    if (ok) {
       uint2 o;
-      o.x = pack_bf16x2(sum.x, sum.y);
-      o.y = pack_bf16x2(sum.z, sum.w);
-      *(uint2*)(C + (long)row * ldc + n0 + col) = o;
+      if (C) {
+        o.x = pack_bf16x2(sum.x, sum.y);
+        o.y = pack_bf16x2(sum.z, sum.w);
+        *(uint2*)(C + (long)row * ldc + n0 + col) = o;
+      }
+      if (scatter) {  // the combine of a one-slot layer, as in the first pass's own stores
+        const float w = weight[it];
+        o.x = pack_bf16x2(__uint_as_float(q.x << 16) + w * sum.x, __uint_as_float(q.x & 0xffff0000u) + w * sum.y);
+        o.y = pack_bf16x2(__uint_as_float(q.y << 16) + w * sum.z, __uint_as_float(q.y & 0xffff0000u) + w * sum.w);
+        *(uint2*)(out + (long)token[it] * ldc + n0 + col) = o;
+      }
     }
   }
 }
@@ -694,13 +776,14 @@ static int32_t launch_mfma(const GemmParams& p, int max_tiles, KernelId id, hipS
   }
   if (max_tiles <= 0) return DYNMO_OK;
   // a product that may split k always brings every compute unit: few tiles is when it splits
-  const bool may_split = (MODE == MODE_DOWN || MODE == MODE_DX) && p.partial != nullptr;
+  const bool may_split = (MODE == MODE_DOWN || MODE == MODE_DOWN_FOLD || MODE == MODE_DX) && p.partial != nullptr;
   const int blocks = persistent_blocks(may_split ? kMaxPersistent : max_tiles);
   ProfScope prof(id, st);
   ffn_mfma_kernel<MODE><<<dim3(blocks), dim3(kMfmaThreads), kLdsBytes + kTableBytes, st>>>(p);
   DYNMO_LAUNCH_CHECK();
   if (may_split) {
-    ffn_split_reduce_kernel<<<dim3(4 * kMaxSplitTiles), dim3(256), 0, st>>>(p.partial, p.C0, p.ldc, p.N);
+    ffn_split_reduce_kernel<<<dim3(4 * kMaxSplitTiles), dim3(256), 0, st>>>(p.partial, p.C0, p.ldc, p.N, p.scatter,
+                                                                            p.scale, p.res, p.out);
     DYNMO_LAUNCH_CHECK();
   }
   return DYNMO_OK;
@@ -713,7 +796,7 @@ bool ffn_mfma_supported(const dynmo_desc* d) {
 
 int32_t ffn_fwd_mfma(const dynmo_desc* d, const void* x_p, const int32_t* gather, const int32_t* seg, const void* Wg,
                      const void* Wu, const void* Wd, void* y_p, void* G, void* U, void* A, void* scratch,
-                     hipStream_t st) {
+                     const FoldedCombine* fc, hipStream_t st) {
   const int mt = max_m_tiles(d, BM);
   const long FH = (long)d->F * d->H;
   GemmParams p = {};
@@ -750,6 +833,13 @@ int32_t ffn_fwd_mfma(const dynmo_desc* d, const void* x_p, const int32_t* gather
   q.b_expert_stride = FH;
   q.C0 = (bf16_t*)y_p;
   q.ldc = d->H;
+  if (fc) {
+    q.scatter = fc->scatter;
+    q.scale = fc->scale;
+    q.res = (const bf16_t*)fc->res;
+    q.out = (bf16_t*)fc->out;
+    return launch_mfma<MODE_DOWN_FOLD>(q, mt * ((d->H + BN - 1) / BN), K_FFN_DOWN, st);
+  }
   return launch_mfma<MODE_DOWN>(q, mt * ((d->H + BN - 1) / BN), K_FFN_DOWN, st);
 }
 

@@ -2,6 +2,8 @@
 
 Holds the device buffers of one layer and issues the library calls in order:
   forward : route -> permute -> grouped_ffn_fwd -> combine
+            (or permute indices only -> grouped_ffn_fwd_gather -> combine,
+             or, for k = 1, permute -> grouped_ffn_fwd_combine)
   backward: combine_bwd -> grouped_ffn_bwd -> permute_bwd -> route_bwd
 Buffers come from torch (device memory only); every step is a library kernel.
 """
@@ -107,6 +109,21 @@ class RoutedFFNLayer:
         B.dynmo_grouped_ffn_fwd_gather(d, x, self.src_slot, self.seg_offsets, Wg, Wu, Wd, self.y_p, self.G, self.U,
                                        self.ws_fwd)
         B.dynmo_combine(d, self.y_p, self.dst_pos, self.gate_w, x if self.residual else None, out)
+        return out
+
+    def forward_folded(self, x, Wg, Wu, Wd, out=None):
+        """k = 1 only: the combine folded into the last product's stores.  A layer with a
+        residual ("mod", "early_exit") updates x in place and returns it: tokens without a
+        routed row are not touched; with `out` given it writes the routed tokens' rows of
+        `out` instead (res = x) and the other rows of `out` are the caller's.  A top-1 "moe"
+        layer writes self.out (every token has a row).  x_p and y_p are still written, so
+        backward() may follow."""
+        d = self.d
+        if out is None:
+            out = x if self.residual else self.out
+        B.dynmo_permute(d, x, self.expert_idx, self.x_p, self.seg_offsets, self.src_slot, self.dst_pos, self.ws_permute)
+        B.dynmo_grouped_ffn_fwd_combine(d, self.x_p, None, self.src_slot, self.seg_offsets, Wg, Wu, Wd, self.gate_w,
+                                        x if self.residual else None, out, self.y_p, self.G, self.U, self.ws_fwd)
         return out
 
     def backward(self, dout, Wg, Wu, Wd, dx=None):

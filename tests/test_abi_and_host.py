@@ -65,6 +65,15 @@ def test_bad_arguments_are_rejected_without_a_gpu():
     big = B.make_desc(300000, 4096, 512, 8, 2, "bf16")  # x is 2.4 GB: beyond the gather call's 32-bit row offsets
     assert lib.dynmo_grouped_ffn_fwd_gather(B.C.byref(big), None, 16, None, None, None, None, None, None, None, None, 0,
                                             None) == -2
+    # the folded combine: two slots per token; both or neither row source; too large to gather
+    fold = lib.dynmo_grouped_ffn_fwd_combine
+    one = B.make_desc(8, 16, 16, 4, 1, "bf16")
+    assert fold(B.C.byref(d), 16, None, 16, 16, 16, 16, 16, 16, None, 16, None, 16, 16, 16, 1 << 30, None) == -1
+    assert fold(B.C.byref(one), 16, 16, 16, 16, 16, 16, 16, 16, None, 16, None, 16, 16, 16, 1 << 30, None) == -1
+    assert fold(B.C.byref(one), None, None, 16, 16, 16, 16, 16, 16, None, 16, None, 16, 16, 16, 1 << 30, None) == -1
+    assert fold(B.C.byref(one), 16, None, 16, 16, 16, 16, 16, None, None, 16, None, 16, 16, 16, 1 << 30, None) == -1
+    big1 = B.make_desc(300000, 4096, 512, 8, 1, "bf16")
+    assert fold(B.C.byref(big1), None, 16, 16, 16, 16, 16, 16, 16, None, 16, None, 16, 16, 16, 1 << 30, None) == -2
     assert lib.dynmo_peak_copy(None, None, 16, None) == -1
     assert lib.dynmo_peak_mfma_bf16(0, None, None, None, None) == -1
     assert lib.dynmo_route_drop_workspace_bytes(B.C.byref(d)) > lib.dynmo_permute_workspace_bytes(B.C.byref(d))

@@ -722,3 +722,107 @@ def test_random_shapes(seed):
     ref = orc.moe_layer(f["logits"], f["x"], f["Wg"], f["Wu"], f["Wd"], w.k, f["dout"])
     assert np.array_equal(to_host(layer.expert_idx), ref["expert_idx"])
     check_layer_full(layer, ref, w.dtype)
+
+
+# --------------------------------------------------------------------------
+# one-slot layers with the combine folded into the last product
+# --------------------------------------------------------------------------
+
+FOLDED_CASES = [
+    ("mod", wl.scaled(wl.CONFIGS[4], T=4 * 256, B=4, S=256, cap=32, H=128, F=256, seed=91)),     # one ragged tile
+    ("mod", wl.scaled(wl.CONFIGS[4], T=3 * 400, B=3, S=400, cap=230, H=520, F=328, seed=92)),    # several tiles, tails
+    ("mod", wl.scaled(wl.CONFIGS[4], T=2 * 330, B=2, S=330, cap=165, H=512, F=1536, seed=93)),   # last product splits k
+    ("mod", wl.scaled(wl.CONFIGS[4], T=2 * 130, B=2, S=130, cap=0, H=64, F=64, seed=94)),        # nothing routed
+    ("mod", wl.scaled(wl.CONFIGS[4], T=2 * 100, B=2, S=100, cap=100, H=36, F=50, dtype="f32", seed=95)),  # fp32 kernels
+    ("moe", wl.scaled(wl.CONFIGS[2], T=330, H=256, F=4096, E=2, k=1, seed=96)),                  # top-1, no residual, split
+    ("moe", wl.scaled(wl.CONFIGS[1], T=300, H=36, F=50, E=4, k=1, seed=97)),                     # top-1 fp32
+]
+
+
+def route_for(layer, mode, w, dev):
+    if mode == "moe":
+        layer.route_topk(dev["logits"])
+    else:
+        layer.route_capacity(dev["scores"], w.cap)
+
+
+@pytest.mark.parametrize("mode,w", FOLDED_CASES,
+                         ids=lambda v: v if isinstance(v, str) else "%s-T%d-H%d-F%d" % (v.dtype, v.T, v.H, v.F))
+def test_forward_with_folded_combine(mode, w):
+    """k = 1: the last product stores res + gate_w * Y straight into the token rows.  Checked
+    against the oracle's layer output; rows of tokens without a routed row keep their bits; the
+    saved tensors are those of the plain forward pass bit for bit, so the backward pass that
+    follows gives identical gradients."""
+    say("folded combine %s %s T=%d H=%d F=%d" % (mode, w.dtype, w.T, w.H, w.F))
+    inp = wl.make_inputs(w, threads=1)
+    dev = {n: to_device(a) for n, a in inp.items()}
+    a = RoutedFFNLayer(w.T, w.H, w.F, w.E, w.k, w.dtype, mode)
+    b = RoutedFFNLayer(w.T, w.H, w.F, w.E, w.k, w.dtype, mode)
+    for layer in (a, b):
+        route_for(layer, mode, w, dev)
+    a.forward(dev["x"], dev["Wg"], dev["Wu"], dev["Wd"])
+    a.backward(dev["dout"], dev["Wg"], dev["Wu"], dev["Wd"])
+    x_b = dev["x"].clone()
+    out_b = b.forward_folded(x_b, dev["Wg"], dev["Wu"], dev["Wd"])
+    assert (out_b is x_b) == (mode != "moe")
+    b.backward(dev["dout"], dev["Wg"], dev["Wu"], dev["Wd"])
+    torch.cuda.synchronize()
+    f = f32_inputs(inp)
+    if mode == "moe":
+        ref = orc.moe_layer(f["logits"], f["x"], f["Wg"], f["Wu"], f["Wd"], w.k, f["dout"])
+    else:
+        ref = orc.mod_layer(f["scores"], w.cap, f["x"], f["Wg"], f["Wu"], f["Wd"], f["dout"])
+    assert np.array_equal(to_host(b.expert_idx), ref["expert_idx"])
+    e_out = assert_close("out", to_host(out_b), ref["out"], TOL[w.dtype])
+    unrouted = torch.as_tensor(ref["expert_idx"][:, 0] < 0, device="cuda")
+    if mode != "moe":
+        assert torch.equal(x_b[unrouted], dev["x"][unrouted])
+    else:
+        assert not bool(unrouted.any())
+    # one rounding instead of two: never further from the plain result than two output steps
+    step = 2.0 ** -7 if w.dtype == "bf16" else 2.0 ** -22
+    assert_close("out vs plain", to_host(out_b), to_host(a.out), 2 * step)
+    R = int(to_host(a.seg_offsets)[-1])
+    for n in ("G", "U", "y_p", "x_p"):
+        assert torch.equal(getattr(a, n)[:R], getattr(b, n)[:R]), n
+    for n in ("dx", "dWg", "dWu", "dWd", "dgate"):
+        assert torch.equal(getattr(a, n), getattr(b, n)), n
+    say("  out err %.1e" % e_out)
+
+    # the same call reading its rows through src_slot, without the unweighted rows, in place
+    x_c = dev["x"].clone()
+    res = x_c if mode != "moe" else None
+    out_c = x_c if mode != "moe" else torch.zeros_like(a.out)
+    G = torch.empty_like(b.G)
+    U = torch.empty_like(b.U)
+    B.dynmo_grouped_ffn_fwd_combine(b.d, None, x_c, b.src_slot, b.seg_offsets, dev["Wg"], dev["Wu"], dev["Wd"],
+                                    b.gate_w, res, out_c, None, G, U, b.ws_fwd)
+    torch.cuda.synchronize()
+    assert torch.equal(out_c, out_b)
+    assert torch.equal(G[:R], b.G[:R]) and torch.equal(U[:R], b.U[:R])
+
+
+def test_folded_combine_early_exit_stack_in_place():
+    """Sec. 2.5's shrinking stack with the residual stream updated in place, layer after layer."""
+    say("folded combine, early-exit stack in place")
+    w = wl.scaled(wl.CONFIGS[5], T=1500, H=128, F=192, seed=98)
+    inp = wl.make_inputs(w, threads=1)
+    dev = {n: to_device(a) for n, a in inp.items()}
+    layers = [RoutedFFNLayer(w.T, w.H, w.F, 1, 1, "bf16", "early_exit") for _ in range(w.layers)]
+    x = dev["x"].clone()
+    for l, layer in enumerate(layers):
+        layer.route_active(dev["exit_layer"], l + 1)
+        assert layer.forward_folded(x, dev["Wg"][l], dev["Wu"][l], dev["Wd"][l]) is x
+    g = dev["dout"]
+    for l in range(w.layers - 1, -1, -1):
+        g = layers[l].backward(g, dev["Wg"][l], dev["Wu"][l], dev["Wd"][l])
+    torch.cuda.synchronize()
+    plain_layers, plain_out, plain_dx = run_stack(w, inp)
+    f = f32_inputs(inp)
+    weights = [(f["Wg"][l], f["Wu"][l], f["Wd"][l]) for l in range(w.layers)]
+    ref = orc.early_exit_stack(inp["exit_layer"], f["x"], weights, f["dout"])
+    assert_close("out", to_host(x), ref["out"], TOL["bf16"])
+    assert_close("dx", to_host(g), ref["dx"], TOL["bf16"])
+    # the in-place stream rounds once per layer where the plain one rounds twice
+    assert_close("out vs plain", to_host(x), to_host(plain_out), 4 * 2.0 ** -7)
+    assert [l.load()[0] for l in layers] == [l.load()[0] for l in plain_layers]
