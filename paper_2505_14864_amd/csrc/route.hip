@@ -121,9 +121,11 @@ __global__ __launch_bounds__(256) void route_topk_ex_kernel(const float* __restr
 }
 
 // ---------------------------------------------------------------------------
-// Capacity top-k: one workgroup per sequence.  A 4-pass, 8-bit-per-pass radix
-// select on order-preserving integer keys finds the cap-th largest score; ties
-// at that value are resolved by ascending position with an ordered block scan.
+// Capacity top-k: one workgroup per sequence.  This kernel takes sequences of any
+// length (the launcher uses it beyond 4096 scores; shorter ones go to the register
+// kernel below).  A 4-pass, 8-bit-per-pass radix select on order-preserving integer
+// keys finds the cap-th largest score; ties at that value are resolved by ascending
+// position with an ordered block scan.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t score_key(float f) {
   uint32_t u = __float_as_uint(f);
@@ -217,6 +219,97 @@ __global__ __launch_bounds__(kCapThreads) void route_capacity_kernel(const float
     __syncthreads();
     if (tid == 0) sh_running += total;
     __syncthreads();
+  }
+}
+
+// The same selection for sequences of at most kRegThreads * KPT scores, whose keys fit in
+// registers (KPT per thread, score i of the sequence in thread i % kRegThreads): the cap-th
+// largest key is found one bit at a time, most significant first -- bit b stays set if at
+// least cap keys are >= the candidate -- with one workgroup-wide count per bit (ballots,
+// four wavefront sums through LDS, one barrier).  No atomics and no serial histogram walk:
+// a few microseconds instead of tens for the 2048-token sequences of the Mixture-of-Depths
+// block.
+constexpr int kRegThreads = 256;
+
+template <int KPT>
+__global__ __launch_bounds__(kRegThreads) void route_capacity_reg_kernel(const float* __restrict__ scores,
+                                                                         int32_t* __restrict__ expert_idx,
+                                                                         float* __restrict__ gate_w, int S, int cap) {
+  constexpr int kWaves = kRegThreads / 64;
+  static_assert(kWaves == 4, "the per-step counts are read back as one int4");
+  static_assert(KPT * kWaves <= 64, "the tie scan below covers one wavefront's worth of partial counts");
+  __shared__ int4 cnt[2];  // per-wavefront counts of one step, double-buffered by step parity
+  __shared__ int eq_cnt[KPT * kWaves];
+  const float* sc = scores + (long)blockIdx.x * S;
+  int32_t* ei = expert_idx + (long)blockIdx.x * S;
+  float* gw = gate_w + (long)blockIdx.x * S;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+
+  float s[KPT];
+  uint32_t key[KPT];
+  bool valid[KPT];
+#pragma unroll
+  for (int j = 0; j < KPT; ++j) {
+    const int i = j * kRegThreads + tid;
+    valid[j] = i < S;
+    s[j] = valid[j] ? sc[i] : 0.f;
+    key[j] = valid[j] ? score_key(s[j]) : 0u;  // candidates below are never 0: padding is not counted
+  }
+  if (cap <= 0 || cap >= S) {
+    const bool all = cap >= S;
+#pragma unroll
+    for (int j = 0; j < KPT; ++j)
+      if (valid[j]) {
+        ei[j * kRegThreads + tid] = all ? 0 : -1;
+        gw[j * kRegThreads + tid] = all ? sigmoidf_(s[j]) : 0.f;
+      }
+    return;
+  }
+
+  // number of keys in the workgroup for which pred holds; `buf` alternates between calls so
+  // that a wavefront one barrier ahead never overwrites counts still being read
+  auto count = [&](auto pred, int buf) {
+    int n = 0;
+#pragma unroll
+    for (int j = 0; j < KPT; ++j) n += __popcll(__ballot(pred(j)));
+    if (lane == 0) ((int*)&cnt[buf])[wv] = n;
+    __syncthreads();
+    const int4 c = cnt[buf];
+    return __builtin_amdgcn_readfirstlane(c.x + c.y + c.z + c.w);
+  };
+
+  uint32_t thr = 0;  // becomes the cap-th largest key
+  for (int b = 31; b >= 0; --b) {
+    const uint32_t cand = thr | (1u << b);
+    if (count([&](int j) { return key[j] >= cand; }, b & 1) >= cap) thr = cand;
+  }
+  const int greater = count([&](int j) { return valid[j] && key[j] > thr; }, 1);
+  const int need_equal = cap - greater;  // ties at the threshold: the first need_equal by position
+
+  unsigned long long eq[KPT];
+#pragma unroll
+  for (int j = 0; j < KPT; ++j) {
+    eq[j] = __ballot(valid[j] && key[j] == thr);
+    if (lane == 0) eq_cnt[j * kWaves + wv] = __popcll(eq[j]);
+  }
+  __syncthreads();
+  // positions ascend with (j, wavefront, lane): exclusive scan of the partial counts in that order
+  const int c = lane < KPT * kWaves ? eq_cnt[lane] : 0;
+  int incl = c;
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) {
+    const int up = __shfl_up(incl, m, 64);
+    if (lane >= m) incl += up;
+  }
+  const int excl = incl - c;
+#pragma unroll
+  for (int j = 0; j < KPT; ++j) {
+    const int before = __shfl(excl, j * kWaves + wv, 64) + __popcll(eq[j] & ((1ull << lane) - 1ull));
+    if (valid[j]) {
+      const bool sel = key[j] > thr || (key[j] == thr && before < need_equal);
+      ei[j * kRegThreads + tid] = sel ? 0 : -1;
+      gw[j * kRegThreads + tid] = sel ? sigmoidf_(s[j]) : 0.f;
+    }
   }
 }
 
@@ -363,9 +456,20 @@ extern "C" int32_t dynmo_route_capacity(const dynmo_desc* d, const float* scores
   if (d->E != 1 || d->k != 1 || B < 0 || S <= 0 || (int64_t)B * S != d->T || cap < 0 || cap > S) return DYNMO_EINVAL;
   if (B > 0) {
     hipStream_t st = (hipStream_t)stream;
-    DYNMO_TIMED_LAUNCH(K_ROUTE_CAPACITY, st,
-                       route_capacity_kernel<<<dim3((unsigned)B), dim3(kCapThreads), 0, st>>>(scores, expert_idx, gate_w,
-                                                                                              S, cap));
+    const dim3 grid((unsigned)B);
+    if (S <= 4 * kRegThreads) {
+      DYNMO_TIMED_LAUNCH(K_ROUTE_CAPACITY, st,
+                         route_capacity_reg_kernel<4><<<grid, dim3(kRegThreads), 0, st>>>(scores, expert_idx, gate_w, S, cap));
+    } else if (S <= 8 * kRegThreads) {
+      DYNMO_TIMED_LAUNCH(K_ROUTE_CAPACITY, st,
+                         route_capacity_reg_kernel<8><<<grid, dim3(kRegThreads), 0, st>>>(scores, expert_idx, gate_w, S, cap));
+    } else if (S <= 16 * kRegThreads) {
+      DYNMO_TIMED_LAUNCH(K_ROUTE_CAPACITY, st,
+                         route_capacity_reg_kernel<16><<<grid, dim3(kRegThreads), 0, st>>>(scores, expert_idx, gate_w, S, cap));
+    } else {
+      DYNMO_TIMED_LAUNCH(K_ROUTE_CAPACITY, st,
+                         route_capacity_kernel<<<grid, dim3(kCapThreads), 0, st>>>(scores, expert_idx, gate_w, S, cap));
+    }
   }
   return DYNMO_OK;
 }

@@ -51,7 +51,8 @@ def test_route_topk(T, E, k, ties):
 
 
 @pytest.mark.parametrize("Bn,S,cap", [(1, 1, 1), (3, 41, 7), (2, 64, 0), (2, 64, 64), (4, 2048, 256), (2, 1024, 1),
-                                      (3, 3000, 1500), (2, 1025, 1024)])
+                                      (3, 3000, 1500), (2, 1025, 1024), (2, 4096, 512), (2, 4097, 100),
+                                      (1, 10000, 3333), (5, 2049, 2048), (2, 1024, 1023)])
 @pytest.mark.parametrize("ties", [False, True])
 def test_route_capacity(Bn, S, cap, ties):
     say("route_capacity B=%d S=%d cap=%d ties=%s" % (Bn, S, cap, ties))
@@ -76,6 +77,31 @@ def test_route_capacity(Bn, S, cap, ties):
     ds = torch.empty((T,), dtype=torch.float32, device="cuda")
     B.dynmo_route_capacity_bwd(d, to_device(dgate), dsc, ei, ds)
     assert_close("dscores", to_host(ds), orc.route_capacity_bwd(dgate, scores, ref_idx), 1e-5)
+
+
+@pytest.mark.parametrize("S,cap", [(2048, 300), (4096, 4095), (700, 1), (5000, 77)])
+def test_route_capacity_degenerate_scores(S, cap):
+    """Every score equal (the first cap positions win), then infinities and denormals around the threshold."""
+    say("route_capacity degenerate S=%d cap=%d" % (S, cap))
+    rng = np.random.default_rng(S + cap)
+    rows = [np.zeros(S, np.float32), np.full(S, -2.5, np.float32)]
+    r = rng.standard_normal(S).astype(np.float32)
+    r[rng.integers(0, S, 5)] = np.inf
+    r[rng.integers(0, S, 5)] = -np.inf
+    r[rng.integers(0, S, 20)] = 1e-42
+    r[rng.integers(0, S, 20)] = -1e-42
+    rows.append(r)
+    scores = np.stack(rows)
+    Bn = len(rows)
+    d = B.make_desc(Bn * S, 8, 8, 1, 1, "bf16")
+    ei = torch.empty((Bn * S, 1), dtype=torch.int32, device="cuda")
+    gw = torch.empty((Bn * S, 1), dtype=torch.float32, device="cuda")
+    B.dynmo_route_capacity(d, to_device(scores), Bn, S, cap, ei, gw)
+    ref_idx, ref_gate = orc.route_capacity(scores, cap)
+    got = to_host(ei)
+    assert np.array_equal(got, ref_idx)
+    assert np.array_equal(np.nonzero(got.reshape(Bn, S)[0] >= 0)[0], np.arange(cap))
+    assert_close("gate_w", to_host(gw), ref_gate, 1e-5)
 
 
 def test_route_active():
