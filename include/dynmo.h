@@ -14,6 +14,8 @@
  *   - outputs are overwritten, never accumulated into.
  *   - `stream` is a hipStream_t (NULL = the default stream).  Calls enqueue work
  *     and return; only dynmo_layer_load synchronises the stream.
+ *   - activation, weight and gradient tensors must be 16-byte aligned (rows move in
+ *     16-byte pieces); a misaligned one gives DYNMO_EINVAL.  Workspaces need no alignment.
  *   - tensors are row-major and contiguous.  T tokens, H hidden size, F FFN size,
  *     E experts, k slots per token; flat slot i = t*k + s.  Index type int32,
  *     -1 = "slot not routed".  R = number of routed slots = seg_offsets[E].

@@ -208,6 +208,7 @@ extern "C" int32_t dynmo_combine(const dynmo_desc* d, const void* y_p, const int
   if (rc) return rc;
   if (!y_p || !dst_pos || !gate_w || !out) return DYNMO_EINVAL;
   if (base == out) return DYNMO_EINVAL;
+  if (misaligned16(y_p, base, out)) return DYNMO_EINVAL;
   if (d->k > kMaxCombineSlots) return DYNMO_EUNSUPPORTED;
   if (d->T == 0) return DYNMO_OK;
   hipStream_t st = (hipStream_t)stream;
@@ -220,6 +221,7 @@ extern "C" int32_t dynmo_combine_bwd(const dynmo_desc* d, const void* dout, cons
   int32_t rc = check_desc(d);
   if (rc) return rc;
   if (!dout || !y_p || !dst_pos || !gate_w || !dy_p || !dgate) return DYNMO_EINVAL;
+  if (misaligned16(dout, y_p, dy_p)) return DYNMO_EINVAL;
   if (d->k > kMaxCombineSlots) return DYNMO_EUNSUPPORTED;
   if (d->T == 0) return DYNMO_OK;
   hipStream_t st = (hipStream_t)stream;

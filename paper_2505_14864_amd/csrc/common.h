@@ -40,6 +40,13 @@ inline int32_t check_desc(const dynmo_desc* d) {
   return DYNMO_OK;
 }
 
+// Row data moves in 16-byte pieces: true if any of the pointers (null ones aside) is not
+// 16-byte aligned.
+template <typename... P>
+inline bool misaligned16(P... ptrs) {
+  return (((uintptr_t)(const void*)ptrs | ...) & 15) != 0;
+}
+
 inline size_t elem_bytes(int32_t dtype) { return dtype == DYNMO_BF16 ? 2 : 4; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

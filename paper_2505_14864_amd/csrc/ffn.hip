@@ -34,6 +34,8 @@ static int32_t ffn_fwd_entry(const dynmo_desc* d, const void* rows, const int32_
   if (rc) return rc;
   if (!rows || !seg_offsets || !Wg || !Wu || !Wd || !G_save || !U_save || !workspace) return DYNMO_EINVAL;
   if (!y_p && !fc) return DYNMO_EINVAL;
+  if (misaligned16(rows, Wg, Wu, Wd, y_p, G_save, U_save) || (fc && misaligned16(fc->res, fc->out)))
+    return DYNMO_EINVAL;
   if (workspace_bytes < dynmo_grouped_ffn_fwd_workspace_bytes(d)) return DYNMO_EWORKSPACE;
   if (max_m_tiles(d, 64) > 65535) return DYNMO_EUNSUPPORTED;
   void* A = (void*)align_up((size_t)workspace, 256);
@@ -85,6 +87,7 @@ extern "C" int32_t dynmo_grouped_ffn_bwd(const dynmo_desc* d, const void* dy_p, 
   if (!dy_p || !x_p || !G_save || !U_save || !seg_offsets || !Wg || !Wu || !Wd || !dx_p || !dWg || !dWu || !dWd ||
       !workspace)
     return DYNMO_EINVAL;
+  if (misaligned16(dy_p, x_p, G_save, U_save, Wg, Wu, Wd, dx_p, dWg, dWu, dWd)) return DYNMO_EINVAL;
   if (workspace_bytes < dynmo_grouped_ffn_bwd_workspace_bytes(d)) return DYNMO_EWORKSPACE;
   if (max_m_tiles(d, 64) > 65535) return DYNMO_EUNSUPPORTED;
   char* base = (char*)align_up((size_t)workspace, 256);

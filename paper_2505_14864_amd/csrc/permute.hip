@@ -260,6 +260,7 @@ extern "C" int32_t dynmo_permute(const dynmo_desc* d, const void* x, const int32
   int32_t rc = check_desc(d);
   if (rc) return rc;
   if (!expert_idx || !seg_offsets || !src_slot || !dst_pos || !workspace || (x_p && !x)) return DYNMO_EINVAL;
+  if (misaligned16(x, x_p)) return DYNMO_EINVAL;
   if (workspace_bytes < dynmo_permute_workspace_bytes(d)) return DYNMO_EWORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   const int n_slots = d->T * d->k;
@@ -336,6 +337,7 @@ extern "C" int32_t dynmo_permute_bwd(const dynmo_desc* d, const void* dx_p, cons
   int32_t rc = check_desc(d);
   if (rc) return rc;
   if (!dx_p || !dst_pos || !dx) return DYNMO_EINVAL;
+  if (misaligned16(dx_p, dbase, dx)) return DYNMO_EINVAL;
   if (d->T == 0) return DYNMO_OK;
   hipStream_t st = (hipStream_t)stream;
   return d->dtype == DYNMO_BF16 ? launch_permute_bwd<bf16_t>(d, dx_p, dst_pos, dbase, dx, st)

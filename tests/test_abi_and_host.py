@@ -74,6 +74,14 @@ def test_bad_arguments_are_rejected_without_a_gpu():
     assert fold(B.C.byref(one), 16, None, 16, 16, 16, 16, 16, None, None, 16, None, 16, 16, 16, 1 << 30, None) == -1
     big1 = B.make_desc(300000, 4096, 512, 8, 1, "bf16")
     assert fold(B.C.byref(big1), None, 16, 16, 16, 16, 16, 16, 16, None, 16, None, 16, 16, 16, 1 << 30, None) == -2
+    # row data moves in 16-byte pieces: a misaligned activation pointer is refused on the host
+    ok = B.make_desc(8, 16, 16, 4, 2, "bf16")
+    assert lib.dynmo_combine(B.C.byref(ok), 32, 16, 16, None, 48 + 2, None) == -1
+    assert lib.dynmo_permute_bwd(B.C.byref(ok), 32 + 8, 16, None, 64, None) == -1
+    assert lib.dynmo_permute(B.C.byref(ok), 32 + 4, 16, 64, 16, 16, 16, 16, 1 << 30, None) == -1
+    assert lib.dynmo_grouped_ffn_fwd(B.C.byref(ok), 32, 16, 64, 96, 128 + 2, 160, 192, 224, 256, 1 << 30, None) == -1
+    assert lib.dynmo_grouped_ffn_bwd(B.C.byref(ok), 32, 64, 96, 128, 16, 160, 192, 224, 256 + 8, 288, 320, 352, 384,
+                                     1 << 30, None) == -1
     assert lib.dynmo_peak_copy(None, None, 16, None) == -1
     assert lib.dynmo_peak_mfma_bf16(0, None, None, None, None) == -1
     assert lib.dynmo_route_drop_workspace_bytes(B.C.byref(d)) > lib.dynmo_permute_workspace_bytes(B.C.byref(d))
