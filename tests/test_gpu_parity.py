@@ -852,3 +852,41 @@ def test_folded_combine_early_exit_stack_in_place():
     # the in-place stream rounds once per layer where the plain one rounds twice
     assert_close("out vs plain", to_host(x), to_host(plain_out), 4 * 2.0 ** -7)
     assert [l.load()[0] for l in layers] == [l.load()[0] for l in plain_layers]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_zero_tokens(dtype):
+    """T = 0: every call on the path returns without touching its (dummy) buffers; the segment
+    offsets come back as zeros, the weight gradients as zeros, the load as zero."""
+    say("zero tokens %s" % dtype)
+    H, F, E, k = 64, 96, 4, 2
+    d = B.make_desc(0, H, F, E, k, dtype)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    dummy = lambda: torch.full((64,), 7, dtype=td, device="cuda")
+    dummy_f = lambda: torch.full((64,), 7.0, dtype=torch.float32, device="cuda")
+    dummy_i = lambda: torch.full((64,), 7, dtype=torch.int32, device="cuda")
+    ei, gw, seg, src, dst = dummy_i(), dummy_f(), dummy_i(), dummy_i(), dummy_i()
+    x, x_p, y_p, G, U, out = dummy(), dummy(), dummy(), dummy(), dummy(), dummy()
+    W = [(torch.randn(E, F, H, device="cuda") * 0.02).to(td), (torch.randn(E, F, H, device="cuda") * 0.02).to(td),
+         (torch.randn(E, H, F, device="cuda") * 0.02).to(td)]
+    ws_p = torch.empty((max(64, B.dynmo_permute_workspace_bytes(d)),), dtype=torch.uint8, device="cuda")
+    ws_f = torch.empty((B.dynmo_grouped_ffn_fwd_workspace_bytes(d),), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty((B.dynmo_grouped_ffn_bwd_workspace_bytes(d),), dtype=torch.uint8, device="cuda")
+    B.dynmo_route_topk(d, dummy_f(), ei, gw)
+    B.dynmo_permute(d, x, ei, x_p, seg, src, dst, ws_p)
+    B.dynmo_grouped_ffn_fwd(d, x_p, seg, W[0], W[1], W[2], y_p, G, U, ws_f)
+    B.dynmo_combine(d, y_p, dst, gw, None, out)
+    dy_p, dgate, dx_p, dx, dl = dummy(), dummy_f(), dummy(), dummy(), dummy_f()
+    dW = [torch.full_like(w, 7) for w in W]
+    B.dynmo_combine_bwd(d, out, y_p, dst, gw, dy_p, dgate)
+    B.dynmo_grouped_ffn_bwd(d, dy_p, x_p, G, U, seg, W[0], W[1], W[2], dx_p, dW[0], dW[1], dW[2], ws_b)
+    B.dynmo_permute_bwd(d, dx_p, dst, None, dx)
+    B.dynmo_route_topk_bwd(d, dgate, gw, ei, dl)
+    counts, load = B.dynmo_layer_load(d, seg, 1.0)
+    torch.cuda.synchronize()
+    assert counts == [0] * E and load == 0.0
+    assert to_host(seg)[:E + 1].tolist() == [0] * (E + 1)
+    for t in (ei, src, dst, x_p, y_p, G, U, out, dy_p, dx_p, dx):
+        assert bool((t == 7).all())
+    for g in dW:
+        assert not bool(g.any())
