@@ -672,47 +672,54 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
 }
 
 // Second pass of a product whose last round was split along k: adds the chunks'
-// partial tiles in chunk order, converts and stores.  One workgroup per quarter tile;
+// partial tiles in chunk order, converts and stores.  One workgroup per 16 rows of a tile
+// (a whole tile per workgroup leaves most compute units idle when few tiles were split);
 // the grid covers the most tiles a split can have, and workgroups beyond what the first
-// pass recorded in the header return at once.
+// pass recorded in the header, or wholly below a ragged tile's last row, return at once.
+constexpr int kReduceRows = 16;                      // rows of a tile per workgroup
+constexpr int kReduceParts = BM / kReduceRows;       // workgroups per tile
+constexpr int kReduceIters = kReduceRows / 4;        // 256 threads cover 4 rows x 256 columns per step
+
 __global__ __launch_bounds__(256) void ffn_split_reduce_kernel(const float* __restrict__ partial, bf16_t* __restrict__ C,
                                                                long ldc, int N, const int32_t* __restrict__ scatter,
                                                                const float* __restrict__ scale, const bf16_t* res,
                                                                bf16_t* out) {
   const int32_t* hdr = (const int32_t*)(partial + kMaxPersistent * kPartialFloats);
   const int split = hdr[0], slots = hdr[2], tiles = hdr[3];
-  const int u = blockIdx.x >> 2, quarter = blockIdx.x & 3;
+  const int u = blockIdx.x / kReduceParts, part = blockIdx.x % kReduceParts;
   if (split <= 1 || u >= tiles) return;
   const int32_t* desc = hdr + 4 + 4 * u;
   const int m0 = desc[0], m_end = desc[1], n0 = desc[2];
+  if (m0 + part * kReduceRows >= m_end) return;
   // chunk c of split tile u was run by workgroup (u % slots) of XCD (u / slots) * split + c
   const float* src = partial + (size_t)((u % slots) * kXcds + (u / slots) * split) * kPartialFloats;
   const int col = (threadIdx.x & 63) * 4;
   const bool cols_ok = n0 + col < N;
-  // folded combine: token index and weight of each of this thread's 16 rows, requested at once
-  int token[16];
-  float weight[16];
+  // folded combine: token index and weight of each of this thread's rows, requested at once
+  int token[kReduceIters];
+  float weight[kReduceIters];
   if (scatter) {
 #pragma unroll
-    for (int it = 0; it < 16; ++it) {
-      const int row = m0 + quarter * 64 + it * 4 + (threadIdx.x >> 6);
+    for (int it = 0; it < kReduceIters; ++it) {
+      const int row = m0 + part * kReduceRows + it * 4 + (threadIdx.x >> 6);
       token[it] = scatter[row < m_end ? row : m0];
     }
 #pragma unroll
-    for (int it = 0; it < 16; ++it) weight[it] = scale[token[it]];
+    for (int it = 0; it < kReduceIters; ++it) weight[it] = scale[token[it]];
   }
 #pragma unroll
-  for (int it = 0; it < 16; ++it) {
-    const int rl = quarter * 64 + it * 4 + (threadIdx.x >> 6);
+  for (int it = 0; it < kReduceIters; ++it) {
+    const int rl = part * kReduceRows + it * 4 + (threadIdx.x >> 6);
     const int row = m0 + rl;
     const bool ok = row < m_end && cols_ok;
+    if (!ok) continue;
     // all chunks' loads are issued before the first add; the sum runs in chunk order
     float4 v[kXcds];
 #pragma unroll
     for (int c = 0; c < kXcds; ++c)
       if (c < split) v[c] = *(const float4*)(src + (size_t)c * kPartialFloats + rl * BN + col);
     uint2 q = make_uint2(0u, 0u);
-    if (scatter && res && ok) q = *(const uint2*)(res + (long)token[it] * ldc + n0 + col);
+    if (scatter && res) q = *(const uint2*)(res + (long)token[it] * ldc + n0 + col);
     float4 sum = v[0];
 #pragma unroll
     for (int c = 1; c < kXcds; ++c)
@@ -722,19 +729,17 @@ __global__ __launch_bounds__(256) void ffn_split_reduce_kernel(const float* __re
         sum.z += v[c].z;
         sum.w += v[c].w;
       }
-    if (ok) {
-      uint2 o;
-      if (C) {
-        o.x = pack_bf16x2(sum.x, sum.y);
-        o.y = pack_bf16x2(sum.z, sum.w);
-        *(uint2*)(C + (long)row * ldc + n0 + col) = o;
-      }
-      if (scatter) {  // the combine of a one-slot layer, as in the first pass's own stores
-        const float w = weight[it];
-        o.x = pack_bf16x2(__uint_as_float(q.x << 16) + w * sum.x, __uint_as_float(q.x & 0xffff0000u) + w * sum.y);
-        o.y = pack_bf16x2(__uint_as_float(q.y << 16) + w * sum.z, __uint_as_float(q.y & 0xffff0000u) + w * sum.w);
-        *(uint2*)(out + (long)token[it] * ldc + n0 + col) = o;
-      }
+    uint2 o;
+    if (C) {
+      o.x = pack_bf16x2(sum.x, sum.y);
+      o.y = pack_bf16x2(sum.z, sum.w);
+      *(uint2*)(C + (long)row * ldc + n0 + col) = o;
+    }
+    if (scatter) {  // the combine of a one-slot layer, as in the first pass's own stores
+      const float w = weight[it];
+      o.x = pack_bf16x2(__uint_as_float(q.x << 16) + w * sum.x, __uint_as_float(q.x & 0xffff0000u) + w * sum.y);
+      o.y = pack_bf16x2(__uint_as_float(q.y << 16) + w * sum.z, __uint_as_float(q.y & 0xffff0000u) + w * sum.w);
+      *(uint2*)(out + (long)token[it] * ldc + n0 + col) = o;
     }
   }
 }
@@ -782,7 +787,7 @@ static int32_t launch_mfma(const GemmParams& p, int max_tiles, KernelId id, hipS
   ffn_mfma_kernel<MODE><<<dim3(blocks), dim3(kMfmaThreads), kLdsBytes + kTableBytes, st>>>(p);
   DYNMO_LAUNCH_CHECK();
   if (may_split) {
-    ffn_split_reduce_kernel<<<dim3(4 * kMaxSplitTiles), dim3(256), 0, st>>>(p.partial, p.C0, p.ldc, p.N, p.scatter,
+    ffn_split_reduce_kernel<<<dim3(kReduceParts * kMaxSplitTiles), dim3(256), 0, st>>>(p.partial, p.C0, p.ldc, p.N, p.scatter,
                                                                             p.scale, p.res, p.out);
     DYNMO_LAUNCH_CHECK();
   }
