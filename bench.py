@@ -406,11 +406,14 @@ def protocol(a, w, inp, dev, layers, Ws, step):
     small = 48 << 20  # bytes each way: the footprint of a config-2 row kernel
     s_src, s_dst = src.view(torch.uint8)[:small], evict.view(torch.uint8)[small:2 * small]
     t_small_warm = min(timed(lambda: B.dynmo_peak_copy(s_dst, s_src)) for _ in range(10))
-    t_small_cold = []
+    t_small_cold, t_small_swept = [], []
     spare = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
     for _ in range(10):
-        spare.fill_(1.0)
+        spare.fill_(1.0)  # leaves the caches full of dirty lines: the call after it also pays for their write-back
         t_small_cold.append(timed(lambda: B.dynmo_peak_copy(s_dst, s_src)))
+    for _ in range(10):
+        spare.sum()       # a read sweep evicts as well, and leaves clean lines
+        t_small_swept.append(timed(lambda: B.dynmo_peak_copy(s_dst, s_src)))
     meas_flops = flops[0] / (t_mfma * 1e-3)
     meas_bw = 2.0 * src.numel() * 4 / (t_copy * 1e-3)
     out["measured_peaks"] = {
@@ -419,11 +422,15 @@ def protocol(a, w, inp, dev, layers, Ws, step):
         "mfma_random_vs_nominal": round(rand_flops / PEAK_BF16_FLOPS, 3),
         "copy_1GiB_GBps": round(meas_bw / 1e9, 1), "copy_vs_nominal": round(meas_bw / PEAK_HBM_BPS, 3),
         "copy_96MiB_warm_GBps": round(2.0 * small / (t_small_warm * 1e-3) / 1e9, 1),
-        "copy_96MiB_cold_GBps": round(2.0 * small / (sorted(t_small_cold)[5] * 1e-3) / 1e9, 1)}
+        "copy_96MiB_cold_GBps": round(2.0 * small / (sorted(t_small_cold)[5] * 1e-3) / 1e9, 1),
+        "copy_96MiB_swept_GBps": round(2.0 * small / (sorted(t_small_swept)[5] * 1e-3) / 1e9, 1)}
     del src
 
     def cold():
         spare.fill_(1.0)
+
+    def swept():
+        spare.sum()
 
     # ---- every kernel inside the forward+backward chain, one repetition at a time
     for _ in range(warm):
@@ -525,7 +532,7 @@ def protocol(a, w, inp, dev, layers, Ws, step):
             idx = names.index(n)
             bytes_ = kernel_work(n, w, rows, w.T)[1]
             ent = {}
-            for label, pre in (("warm", None), ("cold", cold)):
+            for label, pre in (("warm", None), ("cold", cold), ("swept", swept)):
                 xs = []
                 for _ in range(reps):
                     if pre:
@@ -590,7 +597,8 @@ def protocol_text(d, a):
           "  streaming copy, 1 GiB each way                        : %8.1f GB/s     (%s of nominal)" % (
               m["copy_1GiB_GBps"], pct(m["copy_vs_nominal"])),
           "  streaming copy, 48 MiB each way                       : %8.1f GB/s back to back, %.1f GB/s after a "
-          "1 GiB cache-evicting fill" % (m["copy_96MiB_warm_GBps"], m["copy_96MiB_cold_GBps"]), ""]
+          "1 GiB cache-evicting fill, %.1f GB/s after a 1 GiB read sweep" % (
+              m["copy_96MiB_warm_GBps"], m["copy_96MiB_cold_GBps"], m.get("copy_96MiB_swept_GBps", 0.0)), ""]
     L += ["Kernels inside the forward+backward chain (all launches of a role in one pass)",
           "  %-16s %10s %10s  %-5s %9s %9s %12s" % ("kernel", "median", "min", "bound", "nominal", "measured",
                                                    "random-data")]
@@ -608,17 +616,19 @@ def protocol_text(d, a):
         L.append("  its kernels alone (no load export, no host balancer): launched one by one median %.1f, replayed as "
                  "one HIP graph median %.1f" % (e_["median_us"], g_["median_us"]))
     if "hbm_calls_alone" in d:
-        L += ["", "HBM-bound calls alone: warm = back to back, cold = after a 1 GiB fill that evicts L2 and the "
-                  "Infinity Cache",
-              "  %-14s %12s | %8s %9s %8s %9s | %8s %9s %8s %9s" % (
+        L += ["", "HBM-bound calls alone: warm = back to back; cold = after a 1 GiB fill, which evicts L2 and the "
+                  "Infinity Cache and leaves",
+              "them full of dirty lines whose write-back the call then shares the memory with; swept = after a 1 GiB "
+              "read sweep (evicted, clean)",
+              "  %-14s %12s | %8s %9s %8s %9s | %8s %9s %8s | %8s %9s %8s" % (
                   "call", "alg. bytes", "warm us", "GB/s", "nominal", "vs copy", "cold us", "GB/s", "nominal",
-                  "vs copy")]
+                  "swept us", "GB/s", "nominal")]
         for n, e in d["hbm_calls_alone"].items():
-            w_, c_ = e["warm"], e["cold"]
-            L.append("  %-14s %12d | %8.2f %9.1f %8s %9s | %8.2f %9.1f %8s %9s" % (
+            w_, c_, s_ = e["warm"], e["cold"], e.get("swept", e["cold"])
+            L.append("  %-14s %12d | %8.2f %9.1f %8s %9s | %8.2f %9.1f %8s | %8.2f %9.1f %8s" % (
                 n, e["algorithmic_bytes"], w_["median_us"], w_["GBps"], pct(w_["frac_nominal"]),
                 pct(w_["frac_measured_copy"]), c_["median_us"], c_["GBps"], pct(c_["frac_nominal"]),
-                pct(c_["frac_measured_copy"])))
+                s_["median_us"], s_["GBps"], pct(s_["frac_nominal"])))
         L.append("  ('vs copy' is against the 1 GiB copy rate; a copy of the calls' own footprint is two lines up.)")
     if "routing_variants" in d:
         L += ["", "Other routing histograms, same shape (forward+backward chain)"]
