@@ -265,3 +265,23 @@ def test_product_and_oracle_do_not_import_each_other():
     src = open(os.path.join(pkg, "workloads.py")).read()
     for word in ("matmul", "argsort", "softmax", "einsum", " @ "):
         assert word not in src, word
+
+
+def test_bench_reads_measured_traffic_from_the_committed_summary():
+    """roofline.traffic comes from the counter summary under profiles/: the table must parse, give
+    at least the kernel's algorithmic bytes, and give nothing for a kernel or configuration it lacks."""
+    import importlib.util
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    spec = importlib.util.spec_from_file_location("bench_mod2", os.path.join(root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    from paper_2505_14864_amd import workloads as wl
+    w = wl.CONFIGS[2]
+    R = w.T * w.k
+    for name in ("ffn_dX", "ffn_gateup", "ffn_down", "ffn_dA"):
+        got = bench.measured_traffic(2, name)
+        assert got is not None and got > 1e9, name
+    rows_moved = bench.measured_traffic(2, "permute_rows")
+    assert rows_moved is not None and abs(rows_moved - bench.kernel_work("permute_rows", w, R, w.T)[1]) < 0.02 * rows_moved
+    assert bench.measured_traffic(2, "no_such_kernel") is None
+    assert bench.measured_traffic(1, "ffn_dX") is None
