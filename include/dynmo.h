@@ -15,7 +15,8 @@
  *   - `stream` is a hipStream_t (NULL = the default stream).  Calls enqueue work
  *     and return; only dynmo_layer_load synchronises the stream.
  *   - activation, weight and gradient tensors must be 16-byte aligned (rows move in
- *     16-byte pieces); a misaligned one gives DYNMO_EINVAL.  Workspaces need no alignment.
+ *     16-byte pieces); a misaligned one gives DYNMO_EINVAL.  Workspaces need no alignment
+ *     (the *_workspace_bytes values include the slack the library needs to align them).
  *   - tensors are row-major and contiguous.  T tokens, H hidden size, F FFN size,
  *     E experts, k slots per token; flat slot i = t*k + s.  Index type int32,
  *     -1 = "slot not routed".  R = number of routed slots = seg_offsets[E].

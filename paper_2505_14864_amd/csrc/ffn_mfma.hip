@@ -874,6 +874,26 @@ int32_t ffn_bwd_mfma(const dynmo_desc* d, const void* dy_p, const void* x_p, con
     p.U = (const bf16_t*)U;
     if ((rc = launch_mfma<MODE_DA>(p, mt * tF, K_FFN_DA, st))) return rc;
   }
+  // weight gradients: contraction over the rows of each expert
+  auto dw = [&](const void* P, int M, const void* Q, int N, void* out, KernelId id) -> int32_t {
+    GemmParams p = {};
+    p.seg = seg;
+    p.E = d->E;
+    p.M = M;
+    p.N = N;
+    p.A1 = (const bf16_t*)P;
+    p.lda = M;
+    p.B1 = (const bf16_t*)Q;
+    p.ldb = N;
+    p.C0 = (bf16_t*)out;
+    p.ldc = N;
+    return launch_mfma<MODE_DW>(p, d->E * ((M + BM - 1) / BM) * ((N + BN - 1) / BN), id, st);
+  };
+  // Order: the three weight gradients first, dX last, so that the pass that follows the
+  // call (the scatter of dx_p back to token order) finds dx_p still in the last-level cache.
+  if ((rc = dw(dy_p, d->H, A, d->F, dWd, K_FFN_DWD))) return rc;
+  if ((rc = dw(dG, d->F, x_p, d->H, dWg, K_FFN_DWG))) return rc;
+  if ((rc = dw(dU, d->F, x_p, d->H, dWu, K_FFN_DWU))) return rc;
   {  // dX = dG Wg + dU Wu
     GemmParams p = {};
     p.partial = (float*)scratch;
@@ -890,26 +910,8 @@ int32_t ffn_bwd_mfma(const dynmo_desc* d, const void* dy_p, const void* x_p, con
     p.b_expert_stride = FH;
     p.C0 = (bf16_t*)dx_p;
     p.ldc = d->H;
-    if ((rc = launch_mfma<MODE_DX>(p, mt * tH, K_FFN_DX, st))) return rc;
+    return launch_mfma<MODE_DX>(p, mt * tH, K_FFN_DX, st);
   }
-  // weight gradients: contraction over the rows of each expert
-  auto dw = [&](const void* P, int M, const void* Q, int N, void* out, KernelId id) -> int32_t {
-    GemmParams p = {};
-    p.seg = seg;
-    p.E = d->E;
-    p.M = M;
-    p.N = N;
-    p.A1 = (const bf16_t*)P;
-    p.lda = M;
-    p.B1 = (const bf16_t*)Q;
-    p.ldb = N;
-    p.C0 = (bf16_t*)out;
-    p.ldc = N;
-    return launch_mfma<MODE_DW>(p, d->E * ((M + BM - 1) / BM) * ((N + BN - 1) / BN), id, st);
-  };
-  if ((rc = dw(dy_p, d->H, A, d->F, dWd, K_FFN_DWD))) return rc;
-  if ((rc = dw(dG, d->F, x_p, d->H, dWg, K_FFN_DWG))) return rc;
-  return dw(dU, d->F, x_p, d->H, dWu, K_FFN_DWU);
 }
 
 }  // namespace dynmo

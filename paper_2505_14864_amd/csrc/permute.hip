@@ -32,35 +32,50 @@ __global__ __launch_bounds__(kChunkThreads) void permute_count_kernel(const int3
   if (threadIdx.x < E) chunk_counts[blockIdx.x * E + threadIdx.x] = cnt[threadIdx.x];
 }
 
-// One workgroup.  Turns chunk_counts into chunk bases (in place) and writes
-// seg_offsets[E+1].  Thread e walks the chunks of expert e.
-__global__ __launch_bounds__(2 * kMaxExperts) void permute_scan_kernel(int32_t* __restrict__ chunk_counts, int n_chunks, int E,
-                                                                   int32_t* __restrict__ seg_offsets) {
+// One workgroup of sixteen wavefronts.  Turns chunk_counts into chunk bases (in place) and
+// writes seg_offsets[E+1].  A wavefront takes one expert at a time and walks that expert's
+// chunks 64 at a time with a wavefront-wide prefix sum, so the serial depth is
+// n_chunks / 64 steps per expert instead of n_chunks.
+constexpr int kScanThreads = 1024;
+
+__device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int o = __shfl_up(v, d, 64);
+    if (lane >= d) v += o;
+  }
+  return v;
+}
+
+__global__ __launch_bounds__(kScanThreads) void permute_scan_kernel(int32_t* __restrict__ chunk_counts, int n_chunks, int E,
+                                                                    int32_t* __restrict__ seg_offsets) {
+  constexpr int kWaves = kScanThreads / 64;
   __shared__ int total[kMaxExperts];
   __shared__ int seg[kMaxExperts + 1];
-  const int e = threadIdx.x;
-  if (e < E) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int e = wave; e < E; e += kWaves) {
     int s = 0;
-    for (int c = 0; c < n_chunks; ++c) s += chunk_counts[c * E + e];
-    total[e] = s;
+    for (int c = lane; c < n_chunks; c += 64) s += chunk_counts[c * E + e];
+    s = wave_inclusive_scan(s, lane);
+    if (lane == 63) total[e] = s;
   }
   __syncthreads();
-  if (e == 0) {
-    int run = 0;
-    for (int j = 0; j < E; ++j) {
-      seg[j] = run;
-      run += total[j];
-    }
-    seg[E] = run;
+  if (wave == 0) {  // exclusive prefix sum over the experts (E <= 64 = one wavefront)
+    const int v = lane < E ? total[lane] : 0;
+    const int inc = wave_inclusive_scan(v, lane);
+    if (lane < E) seg[lane] = inc - v;
+    if (lane == E - 1) seg[E] = inc;
   }
   __syncthreads();
-  if (e <= E) seg_offsets[e] = seg[e];
-  if (e < E) {
+  if (threadIdx.x <= E) seg_offsets[threadIdx.x] = seg[threadIdx.x];
+  for (int e = wave; e < E; e += kWaves) {
     int run = seg[e];
-    for (int c = 0; c < n_chunks; ++c) {
-      const int v = chunk_counts[c * E + e];
-      chunk_counts[c * E + e] = run;
-      run += v;
+    for (int c0 = 0; c0 < n_chunks; c0 += 64) {
+      const int c = c0 + lane;
+      const int v = c < n_chunks ? chunk_counts[c * E + e] : 0;
+      const int inc = wave_inclusive_scan(v, lane);
+      if (c < n_chunks) chunk_counts[c * E + e] = run + inc - v;
+      run += __shfl(inc, 63, 64);
     }
   }
 }
@@ -251,28 +266,23 @@ using namespace dynmo;
 
 extern "C" size_t dynmo_permute_workspace_bytes(const dynmo_desc* d) {
   if (check_desc(d)) return 0;
-  return align_up((size_t)(n_chunks_of(d) > 0 ? n_chunks_of(d) : 1) * d->E * sizeof(int32_t), 256);
+  // the chunk histograms, plus slack to align whatever address the caller hands over
+  return align_up((size_t)(n_chunks_of(d) > 0 ? n_chunks_of(d) : 1) * d->E * sizeof(int32_t), 256) + 256;
 }
 
-extern "C" int32_t dynmo_permute(const dynmo_desc* d, const void* x, const int32_t* expert_idx, void* x_p,
-                                 int32_t* seg_offsets, int32_t* src_slot, int32_t* dst_pos, void* workspace,
-                                 size_t workspace_bytes, void* stream) {
-  int32_t rc = check_desc(d);
-  if (rc) return rc;
-  if (!expert_idx || !seg_offsets || !src_slot || !dst_pos || !workspace || (x_p && !x)) return DYNMO_EINVAL;
-  if (misaligned16(x, x_p)) return DYNMO_EINVAL;
-  if (workspace_bytes < dynmo_permute_workspace_bytes(d)) return DYNMO_EWORKSPACE;
-  hipStream_t st = (hipStream_t)stream;
+namespace dynmo {
+// The permutation proper; chunk_counts holds n_chunks * E ints of scratch (fully rewritten).
+static int32_t permute_run(const dynmo_desc* d, const void* x, const int32_t* expert_idx, void* x_p, int32_t* seg_offsets,
+                           int32_t* src_slot, int32_t* dst_pos, int32_t* chunk_counts, hipStream_t st) {
   const int n_slots = d->T * d->k;
   const int nc = n_chunks_of(d);
-  int32_t* chunk_counts = (int32_t*)workspace;
   if (nc > 0) {
     DYNMO_TIMED_LAUNCH(K_PERMUTE_COUNT, st,
                        permute_count_kernel<<<dim3(nc), dim3(kChunkThreads), 0, st>>>(expert_idx, n_slots, d->E,
                                                                                       chunk_counts));
   }
   DYNMO_TIMED_LAUNCH(K_PERMUTE_SCAN, st,
-                     permute_scan_kernel<<<dim3(1), dim3(2 * kMaxExperts), 0, st>>>(chunk_counts, nc, d->E, seg_offsets));
+                     permute_scan_kernel<<<dim3(1), dim3(kScanThreads), 0, st>>>(chunk_counts, nc, d->E, seg_offsets));
   if (nc == 0) return DYNMO_OK;
   DYNMO_TIMED_LAUNCH(K_PERMUTE_SCATTER, st,
                      permute_scatter_kernel<<<dim3(nc), dim3(kChunkThreads), 0, st>>>(expert_idx, n_slots, d->E,
@@ -281,6 +291,27 @@ extern "C" int32_t dynmo_permute(const dynmo_desc* d, const void* x, const int32
   if (d->k <= 2) return launch_rows<2>(d, x, dst_pos, x_p, st);
   if (d->k <= 8) return launch_rows<8>(d, x, dst_pos, x_p, st);
   return launch_rows<kMaxExperts>(d, x, dst_pos, x_p, st);
+}
+
+static int32_t permute_check(const dynmo_desc* d, const void* x, const int32_t* expert_idx, void* x_p, int32_t* seg_offsets,
+                             int32_t* src_slot, int32_t* dst_pos) {
+  int32_t rc = check_desc(d);
+  if (rc) return rc;
+  if (!expert_idx || !seg_offsets || !src_slot || !dst_pos || (x_p && !x)) return DYNMO_EINVAL;
+  if (misaligned16(x, x_p)) return DYNMO_EINVAL;
+  return DYNMO_OK;
+}
+}  // namespace dynmo
+
+extern "C" int32_t dynmo_permute(const dynmo_desc* d, const void* x, const int32_t* expert_idx, void* x_p,
+                                 int32_t* seg_offsets, int32_t* src_slot, int32_t* dst_pos, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  int32_t rc = permute_check(d, x, expert_idx, x_p, seg_offsets, src_slot, dst_pos);
+  if (rc) return rc;
+  if (!workspace) return DYNMO_EINVAL;
+  if (workspace_bytes < dynmo_permute_workspace_bytes(d)) return DYNMO_EWORKSPACE;
+  int32_t* chunk_counts = (int32_t*)align_up((size_t)workspace, 256);
+  return permute_run(d, x, expert_idx, x_p, seg_offsets, src_slot, dst_pos, chunk_counts, (hipStream_t)stream);
 }
 
 namespace dynmo {
