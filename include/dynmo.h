@@ -139,6 +139,21 @@ int32_t dynmo_permute(const dynmo_desc* d, const void* x, const int32_t* expert_
                       int32_t* seg_offsets, int32_t* src_slot, int32_t* dst_pos, void* workspace,
                       size_t workspace_bytes, void* stream);
 
+/* dynmo_permute for callers that cannot allocate device memory or hand over a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc):
+ * same arguments, results and kernels as dynmo_permute, but the scratch (the per-chunk
+ * expert histograms) lives in a fixed 1 MiB device array inside the library, one copy per
+ * GPU, held until the process ends.  The call allocates and frees nothing.  Limit:
+ * ceil(T*k / 1024) * E <= 262144, i.e. T*k <= dynmo_permute_static_max_slots(E) slots
+ * (4 194 304 slots at E = 64, 33 554 432 at E = 8); beyond it DYNMO_EWORKSPACE is returned
+ * and nothing is launched.  Nothing in the array has to start at zero (every entry that
+ * is read is rewritten first), but all calls on one GPU share it: two calls that overlap
+ * in time on the same GPU (different streams or threads) race.  Calls on one stream, or
+ * otherwise ordered, are fine. */
+size_t dynmo_permute_static_max_slots(int32_t E);
+int32_t dynmo_permute_static(const dynmo_desc* d, const void* x, const int32_t* expert_idx, void* x_p,
+                             int32_t* seg_offsets, int32_t* src_slot, int32_t* dst_pos, void* stream);
+
 /* Backward of permute (and of the pass-through residual when dbase != NULL):
  * dx[t] = dbase[t] + sum over routed slots s of dx_p[dst_pos[t,s]].
  * dx_p [T*k,H], dst_pos [T,k], dbase [T,H] or NULL -> dx [T,H]. */

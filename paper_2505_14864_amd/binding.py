@@ -52,6 +52,8 @@ SIGNATURES = {
     "dynmo_route_drop": (_I, [_D, _P, _I, _P, _P, C.c_size_t, _P]),
     "dynmo_permute_workspace_bytes": (C.c_size_t, [_D]),
     "dynmo_permute": (_I, [_D, _P, _P, _P, _P, _P, _P, _P, C.c_size_t, _P]),
+    "dynmo_permute_static_max_slots": (C.c_size_t, [_I]),
+    "dynmo_permute_static": (_I, [_D, _P, _P, _P, _P, _P, _P, _P]),
     "dynmo_permute_bwd": (_I, [_D, _P, _P, _P, _P, _P]),
     "dynmo_grouped_ffn_fwd_workspace_bytes": (C.c_size_t, [_D]),
     "dynmo_grouped_ffn_fwd": (_I, [_D, _P, _P, _P, _P, _P, _P, _P, _P, _P, C.c_size_t, _P]),
@@ -180,6 +182,16 @@ def dynmo_permute(d, x, expert_idx, x_p, seg_offsets, src_slot, dst_pos, workspa
     _check("dynmo_permute", lib().dynmo_permute(C.byref(d), _ptr(x), _ptr(expert_idx), _ptr(x_p), _ptr(seg_offsets),
                                                 _ptr(src_slot), _ptr(dst_pos), _ptr(workspace), workspace.numel(),
                                                 _stream(stream)))
+
+
+def dynmo_permute_static_max_slots(E):
+    return lib().dynmo_permute_static_max_slots(int(E))
+
+
+def dynmo_permute_static(d, x, expert_idx, x_p, seg_offsets, src_slot, dst_pos, stream=None):
+    _check("dynmo_permute_static", lib().dynmo_permute_static(C.byref(d), _ptr(x), _ptr(expert_idx), _ptr(x_p),
+                                                              _ptr(seg_offsets), _ptr(src_slot), _ptr(dst_pos),
+                                                              _stream(stream)))
 
 
 def dynmo_permute_bwd(d, dx_p, dst_pos, dbase, dx, stream=None):

@@ -4,6 +4,8 @@
 // from wavefront ballots.  The row movement is a token-centric copy: each source
 // row is read once and written to its (up to k) destinations with 16-byte
 // accesses.
+#include <mutex>
+
 #include "common.h"
 #include "profile.h"
 
@@ -311,6 +313,61 @@ extern "C" int32_t dynmo_permute(const dynmo_desc* d, const void* x, const int32
   if (!workspace) return DYNMO_EINVAL;
   if (workspace_bytes < dynmo_permute_workspace_bytes(d)) return DYNMO_EWORKSPACE;
   int32_t* chunk_counts = (int32_t*)align_up((size_t)workspace, 256);
+  return permute_run(d, x, expert_idx, x_p, seg_offsets, src_slot, dst_pos, chunk_counts, (hipStream_t)stream);
+}
+
+// ---- the permutation for callers that cannot allocate ------------------------------
+// The chunk histograms live in a file-scope device array instead of a caller workspace.
+// Every device the library runs on holds its own copy at its own address, which is looked
+// up once per device (with that device current) and used from then on; the array's name
+// itself is only a host-side handle and is never passed to a kernel.
+namespace dynmo {
+constexpr size_t kStaticScratchInts = (size_t)1 << 18;  // 1 MiB: 4096 chunks of 1024 slots x 64 experts
+static __device__ __align__(256) int32_t scratch[kStaticScratchInts];
+
+constexpr int kMaxScratchDevices = 64;
+static std::mutex g_scratch_mutex;
+static int32_t* g_scratch_ptr[kMaxScratchDevices] = {};
+
+// the calling thread's current device's copy of `scratch`, or nullptr with *rc set
+static int32_t* static_scratch(int32_t* rc) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) {
+    *rc = hip_fail(e);
+    return nullptr;
+  }
+  if (dev < 0 || dev >= kMaxScratchDevices) {
+    *rc = DYNMO_EUNSUPPORTED;
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      *rc = hip_fail(e != hipSuccess ? e : hipErrorInvalidSymbol);
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = (int32_t*)ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace dynmo
+
+extern "C" size_t dynmo_permute_static_max_slots(int32_t E) {
+  if (E <= 0 || E > kMaxExperts) return 0;
+  return kStaticScratchInts / (size_t)E * kChunk;
+}
+
+extern "C" int32_t dynmo_permute_static(const dynmo_desc* d, const void* x, const int32_t* expert_idx, void* x_p,
+                                        int32_t* seg_offsets, int32_t* src_slot, int32_t* dst_pos, void* stream) {
+  int32_t rc = permute_check(d, x, expert_idx, x_p, seg_offsets, src_slot, dst_pos);
+  if (rc) return rc;
+  if ((size_t)n_chunks_of(d) * d->E > kStaticScratchInts) return DYNMO_EWORKSPACE;  // beyond the fixed scratch
+  int32_t* chunk_counts = static_scratch(&rc);
+  if (!chunk_counts) return rc;
+  // nothing to clear: the count kernel rewrites every histogram entry the later kernels read
   return permute_run(d, x, expert_idx, x_p, seg_offsets, src_slot, dst_pos, chunk_counts, (hipStream_t)stream);
 }
 
