@@ -12,12 +12,16 @@
 // each, as 2x4 v_mfma_f32_32x32x16_bf16 blocks = 128 accumulator registers per
 // lane), K in steps of 64 through two LDS stages.  Two wavefronts share each SIMD:
 // one wavefront alone cannot issue MFMAs back to back (measured 87% of the MFMA
-// rate, against 99% with two).  Tiles whose memory layout has
-// K contiguous are kept [row][k] in LDS (row pitch 144 B, conflict-free 16-byte
-// fragment reads); tiles whose memory layout has the row index contiguous are
-// kept [k][row] (pitch 576 B) and read with ds_read_b64_tr_b16, which hands each
-// lane four consecutive k of one row -- so no operand is ever transposed in
-// HBM or by scalar LDS traffic.
+// rate, against 99% with two).  Operand tiles go from global memory straight into
+// LDS (buffer loads with an LDS destination, 1 KB per wavefront instruction), one
+// such load per MFMA slot: no staging registers, no LDS store instructions, and no
+// burst of memory instructions that would hold up a wavefront's MFMAs.  The tiles
+// are unpadded and swizzled instead: the loads place each 16-byte piece where the
+// fragment reads are free of bank conflicts.  Tiles whose memory layout has K
+// contiguous are kept [row][k] in LDS; tiles whose memory layout has the row index
+// contiguous are kept [k][row] and read with ds_read_b64_tr_b16, which hands each
+// lane four consecutive k of one row -- so no operand is ever transposed in HBM or
+// by scalar LDS traffic.
 //
 // Ragged rows: the row-tile list is derived on the device from seg_offsets, so
 // no host synchronisation is needed.  One persistent workgroup per compute unit
@@ -43,14 +47,14 @@ typedef __attribute__((ext_vector_type(8))) short s16x8_t;
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int kMfmaThreads = 512;              // eight wavefronts: two per SIMD
-constexpr int kPieces = 2048 / kMfmaThreads;   // 16-byte pieces of a staged tile per thread
-constexpr int kPitchK = 144;                 // bytes per row of a [row][k] tile: 64 bf16 + 16 pad
-constexpr int kPitchT = 576;                 // bytes per k-row of a [k][row] tile: 256 bf16 + 64 pad
-constexpr int kTileBytes = 256 * kPitchK;    // == 64 * kPitchT == 36864
-constexpr int kLdsBytes = 4 * kTileBytes;    // two stages of (A, B)
-constexpr int kTableBytes = 64 * 8 * 4;      // the per-expert tile table, kept behind the stages
-constexpr int kEpPitch = 136;                // floats per row of an epilogue LDS patch (128 + 8 pad)
+constexpr int kWaves = kMfmaThreads / 64;
+constexpr int kPieces = 32 / kWaves;           // 1 KB pieces of an operand tile per wavefront
+constexpr int kTileBytes = 256 * 64 * 2;       // one operand tile (256 rows x 64 k, bf16), unpadded
+constexpr int kStageBytes = 2 * kTileBytes;    // A then B
+constexpr int kEpPitch = 136;                  // floats per row of an epilogue LDS patch (128 + 8 pad)
 constexpr int kEpWaveBytes = 32 * kEpPitch * 4;  // one 32-row band per wavefront
+constexpr int kLdsBytes = kWaves * kEpWaveBytes;  // the epilogue patches; the two stages fit inside
+constexpr int kTableBytes = 64 * 8 * 4;        // the per-expert tile table, kept behind them
 constexpr int kXcds = 8;
 constexpr int kGroupN = 8;                   // column tiles that run side by side in one XCD
 constexpr int kMaxPersistent = 256;          // persistent workgroups per launch (one per compute unit)
@@ -59,8 +63,8 @@ constexpr int kMaxSplitTiles = kMaxPersistent / 2;     // tiles of a last round 
 constexpr size_t kPartialFloats = (size_t)BM * BN;     // one workgroup's fp32 partial tile
 constexpr int kSplitHdrInts = 4 + 4 * kMaxSplitTiles;  // {split, patches, slots, tiles} + {m0, m_end, n0, -} per tile
 
-static_assert(256 * kPitchK == 64 * kPitchT, "both tile layouts must have the same size");
-static_assert((kMfmaThreads / 64) * kEpWaveBytes <= kLdsBytes, "epilogue patches must fit in the staging buffers");
+static_assert(2 * kStageBytes <= kLdsBytes, "the two stages must fit in front of the tile table");
+static_assert(kPieces * kWaves == 32, "a tile is 32 pieces of 1 KB");
 
 // MODE_DOWN_FOLD is MODE_DOWN with the weighted combine of a one-slot layer in its stores
 enum { MODE_GATEUP = 0, MODE_DOWN = 1, MODE_DA = 2, MODE_DX = 3, MODE_DW = 4, MODE_DOWN_FOLD = 5 };
@@ -95,22 +99,52 @@ struct GemmParams {
   bf16_t* out;
 };
 
-// ---- global -> registers -> LDS staging ---------------------------------------
-// A staged tile is 256 "rows" x 64 k.  Each thread moves eight 16-byte pieces with
-// raw buffer loads: a piece outside the valid rows / k range is given an offset
-// beyond the buffer's record count, for which the hardware returns zeros, so the
-// loads are branch-free.  Every offset that is not masked this way lies inside the
-// operand.  The buffer base already points at the tile's (row0, k0) element.
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
+// ---- global memory -> LDS ---------------------------------------------------------
+// An operand tile is 256 "rows" x 64 k = 32 pieces of 1 KB.  One buffer load with an
+// LDS destination moves a piece: lane l fetches 16 bytes from its own global offset and
+// the hardware drops them at (LDS base of the piece) + 16 l.  A piece outside the valid
+// rows / k range is given an offset beyond the buffer's record count, for which the
+// hardware delivers zeros, so the loads are branch-free.  Every offset that is not masked
+// this way lies inside the operand.  The buffer base already points at the tile's
+// (row0, k0) element.
+//
+// LDS layouts (unpadded; the swizzles make the fragment reads below conflict-free):
+//   [row][k]: 128 bytes per row; the 16-byte piece with k = 8 c .. 8 c + 7 of row r sits at
+//             r * 128 + ((c ^ ((r >> 1) & 7)) << 4)
+//   [k][row]: 512 bytes per k-row in eight 64-byte blocks of 32 rows; block b of k-row k
+//             sits at k * 512 + (((b & 4) | ((b ^ k) & 3)) << 6)
 constexpr uint32_t kOob = 0x80000000u;
 
-__device__ __forceinline__ rsrc_t make_rsrc(const bf16_t* p) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(p), 0, 0x7ffffffe, 0x00020000);
+// raw buffer descriptor (wave-uniform): base address, stride 0, record count in bytes
+typedef uint32_t desc_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ desc_t make_desc(const bf16_t* p, uint32_t bytes) {
+  const uint64_t a = (uint64_t)p;
+  desc_t d;
+  d.x = (uint32_t)a;
+  d.y = (uint32_t)(a >> 32) & 0xffffu;
+  d.z = bytes;
+  d.w = 0x00020000u;
+  return d;
 }
 
-__device__ __forceinline__ u32x4 bload(rsrc_t rs, uint32_t off) {
-  return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0));
+// One piece: global -> LDS.  Written as assembly so that the compiler sees neither a
+// load (it would count it against its own waits) nor an LDS write (it would make every
+// transposed LDS read wait for all outstanding loads); the k loop waits for these loads
+// itself, once per k tile.  The memory clobber keeps LDS reads from moving across it.
+__device__ __forceinline__ void load_to_lds(desc_t d, uint32_t lds_offset, uint32_t global_offset) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               :
+               : "s"(lds_offset), "v"(global_offset), "s"(d)
+               : "memory");
 }
+
+// Waits of the k loop, written out because the loads above are invisible to the compiler.
+__device__ __forceinline__ void wait_loads_and_lds() { __builtin_amdgcn_s_waitcnt(0x0070); }  // vmcnt(0) lgkmcnt(0)
+template <int N>
+__device__ __forceinline__ void wait_loads_but() {  // at most N loads still in flight
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0f70);
+}
+__device__ __forceinline__ void wg_barrier() { __builtin_amdgcn_s_barrier(); }
 
 // The thread index behind a compiler barrier.  Offsets derived from it are recomputed where
 // they are used (once per output tile) instead of being computed at kernel entry and kept
@@ -121,69 +155,66 @@ __device__ __forceinline__ int tid_now() {
   return t;
 }
 
-// Per-thread offsets of the eight pieces of a staged tile.  Row validity does not
-// change along k, so it is folded into the offsets once per output tile; the k
-// validity is applied per k tile (it only bites in a ragged last tile).
+// Per-lane global offsets of the pieces a wavefront moves: piece j of wavefront w is piece
+// w * kPieces + j of the tile.  Row validity does not change along k, so it is folded into
+// the offsets once per output tile; the k validity is applied per k tile (it only bites in
+// a ragged last tile).
 struct Pieces {
   uint32_t off[kPieces];  // byte offset from the tile's (row0, k0) element, or kOob
-  int kpos[kPieces];      // k index of the piece inside the 64-wide k tile
+  int kpos[kPieces];      // k index of the lane's 16 bytes inside the 64-wide k tile
 };
 
-// [row][k] memory: piece j of a thread is row tid/8 + 64 j, k offset (tid%8)*8.
-// `wrap` = 128 for the gate/up pairing (pieces 4..7 repeat rows 0..127 of a second matrix).
+// [row][k] memory: piece q holds LDS rows 8 q .. 8 q + 7; lane l fills slot l % 8 of row
+// 8 q + l / 8, which the swizzle assigns to k piece (l % 8) ^ ((row >> 1) & 7).
+// `wrap` = 128 for the gate/up pairing (LDS rows 128..255 are rows 0..127 of a second matrix).
 __device__ __forceinline__ Pieces pieces_rowk(uint32_t ld_bytes, int rows_left, int wrap) {
   Pieces ps;
   const int tid = tid_now();
-  const int r0 = tid >> 3, kc = (tid & 7) * 8;
+  const int lane = tid & 63, wave = tid >> 6;
 #pragma unroll
   for (int j = 0; j < kPieces; ++j) {
-    const int row = (r0 + (kMfmaThreads / 8) * j) % wrap;
-    ps.off[j] = row < rows_left ? (uint32_t)row * ld_bytes + kc * 2 : kOob;
-    ps.kpos[j] = kc;
+    const int lrow = (wave * kPieces + j) * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((lrow >> 1) & 7);
+    const int row = lrow % wrap;
+    ps.off[j] = row < rows_left ? (uint32_t)row * ld_bytes + c * 16 : kOob;
+    ps.kpos[j] = c * 8;
   }
   return ps;
 }
 
-// [k][row] memory: piece j of a thread is k-row tid/32 + 16 j, row offset (tid%32)*8
+// [k][row] memory: piece q holds k-rows 2 q and 2 q + 1; lane l fills 16-byte slot l % 32 of
+// k-row 2 q + l / 32, i.e. quarter (l % 4) of stored block (l % 32) / 4.
 __device__ __forceinline__ Pieces pieces_krow(uint32_t ld_bytes, int rows_left) {
   Pieces ps;
   const int tid = tid_now();
-  const int k0 = tid >> 5, rc = (tid & 31) * 8;
+  const int lane = tid & 63, wave = tid >> 6;
 #pragma unroll
   for (int j = 0; j < kPieces; ++j) {
-    ps.off[j] = rc < rows_left ? (uint32_t)(k0 + (kMfmaThreads / 32) * j) * ld_bytes + rc * 2 : kOob;
-    ps.kpos[j] = k0 + (kMfmaThreads / 32) * j;
+    const int k = (wave * kPieces + j) * 2 + (lane >> 5);
+    const int slot = lane & 31, stored = slot >> 2;
+    const int blk = (stored & 4) | ((stored ^ k) & 3);
+    const int col = blk * 32 + (slot & 3) * 8;
+    ps.off[j] = col < rows_left ? (uint32_t)k * ld_bytes + col * 2 : kOob;
+    ps.kpos[j] = k;
   }
   return ps;
 }
 
-__device__ __forceinline__ u32x4 load_piece(rsrc_t rs, const Pieces& ps, int j, int k_left) {
-  return bload(rs, ps.kpos[j] < k_left ? ps.off[j] : kOob);
-}
-
-template <bool TRANS>
-__device__ __forceinline__ void store_piece(char* tile, const u32x4& v, int j) {
-  const int c = threadIdx.x + kMfmaThreads * j;
-  if (!TRANS)
-    *(u32x4*)(tile + (c >> 3) * kPitchK + (c & 7) * 16) = v;
-  else
-    *(u32x4*)(tile + (c >> 5) * kPitchT + (c & 31) * 16) = v;
-}
-
-// [row][k] memory whose rows are fetched through an index: piece j is row
-// rowmap[row0 + tid/8 + 64 j] / rowdiv of the operand, so the offsets are taken from the
-// operand's first row (the buffer base then points at (row 0, k0)).
+// [row][k] memory whose rows are fetched through an index: LDS row r is row
+// rowmap[row0 + r] / rowdiv of the operand, so the offsets are taken from the operand's
+// first row (the buffer base then points at (row 0, k0)).
 __device__ __forceinline__ Pieces pieces_rowk_gather(uint32_t ld_bytes, int row0, int rows_left,
                                                      const int32_t* __restrict__ rowmap, int rowdiv) {
   Pieces ps;
   const int tid = tid_now();
-  const int r0 = tid >> 3, kc = (tid & 7) * 8;
+  const int lane = tid & 63, wave = tid >> 6;
 #pragma unroll
   for (int j = 0; j < kPieces; ++j) {
-    const int row = r0 + (kMfmaThreads / 8) * j;
+    const int lrow = (wave * kPieces + j) * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((lrow >> 1) & 7);
     ps.off[j] = kOob;
-    if (row < rows_left) ps.off[j] = (uint32_t)(rowmap[row0 + row] / rowdiv) * ld_bytes + kc * 2;
-    ps.kpos[j] = kc;
+    if (lrow < rows_left) ps.off[j] = (uint32_t)(rowmap[row0 + lrow] / rowdiv) * ld_bytes + c * 16;
+    ps.kpos[j] = c * 8;
   }
   return ps;
 }
@@ -191,22 +222,52 @@ __device__ __forceinline__ Pieces pieces_rowk_gather(uint32_t ld_bytes, int row0
 // ---- LDS -> MFMA operand fragments ---------------------------------------------
 // Operand of v_mfma_f32_32x32x16_bf16: lane l holds, for row (l % 32) of the 32-row
 // block, the eight k values (l / 32) * 8 .. + 7 of the 16-wide k step.
+//
+// Per-lane byte addresses (inside an operand tile) from which every fragment of a k tile is
+// reached by adding a compile-time constant.  [row][k] tiles: one address per k step (the
+// swizzle mixes the k piece into the address; the 32-row block adds block * 4096).
+// [k][row] tiles: one address per 32-row block (the swizzle mixes the block into the
+// address; the k step adds step * 16 * 512).  `first_block` is the wavefront's first block;
+// `block_of[i]` the i-th block it reads, relative to it.
+struct FragAddr {
+  uint32_t a[4];
+};
+
 template <bool TRANS>
-__device__ __forceinline__ bf16x8_t lfrag(const char* tile, int blk, int ks) {
-  const int lane = threadIdx.x & 63;
+__device__ __forceinline__ FragAddr frag_addr(int first_block, const int (&block_of)[4]) {
+  FragAddr fa;
+  const int lane = tid_now() & 63;
   if (!TRANS) {
-    const int off = (blk * 32 + (lane & 31)) * kPitchK + ks * 32 + (lane >> 5) * 16;
-    return *(const bf16x8_t*)(tile + off);
+    const int r = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+      fa.a[ks] = (uint32_t)((first_block * 32 + r) * 128 + (((ks * 2 + h) ^ ((r >> 1) & 7)) << 4));
   } else {
-    // ds_read_b64_tr_b16 works on groups of 16 lanes: lane s of a group points at
-    // four consecutive rows (s % 4) * 4 .. + 3 of k-row (s / 4); afterwards lane i
-    // of the group holds row i for those four k-rows.
-    const int s = lane & 15;
-    const int col = blk * 32 + ((lane >> 4) & 1) * 16 + (s & 3) * 4;
-    const int k = ks * 16 + (lane >> 5) * 8 + (s >> 2);
+    // ds_read_b64_tr_b16 works on groups of 16 lanes: lane s of a group points at four
+    // consecutive rows (s % 4) * 4 .. + 3 of k-row (s / 4); afterwards lane i of the group
+    // holds row i for those four k-rows.
+    const int s = lane & 15, h = lane >> 5;
+    const int k = h * 8 + (s >> 2);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int blk = first_block + block_of[i];
+      const int stored = (blk & 4) | ((blk ^ k) & 3);
+      fa.a[i] = (uint32_t)(k * 512 + stored * 64 + (((lane >> 4) & 1) * 16 + (s & 3) * 4) * 2);
+    }
+  }
+  return fa;
+}
+
+// Fragment `i` (the i-th block the wavefront reads, at relative block BLK) of k step KS.
+template <bool TRANS, int BLK, int KS>
+__device__ __forceinline__ bf16x8_t lfrag(const char* tile, const FragAddr& fa, int i) {
+  if (!TRANS) {
+    return *(const bf16x8_t*)(tile + fa.a[KS] + BLK * 4096);
+  } else {
     typedef __attribute__((address_space(3))) s16x4_t* lds_ptr;
-    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(tile + k * kPitchT + col * 2));
-    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(tile + (k + 4) * kPitchT + col * 2));
+    const char* q = tile + fa.a[i] + KS * 16 * 512;
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)q);
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(q + 4 * 512));
     s16x8_t v;
     v.s0 = lo.x; v.s1 = lo.y; v.s2 = lo.z; v.s3 = lo.w;
     v.s4 = hi.x; v.s5 = hi.y; v.s6 = hi.z; v.s7 = hi.w;
@@ -402,19 +463,20 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
 
   // ---- main loop -------------------------------------------------------------
   // A hand-ordered software pipeline; __builtin_amdgcn_sched_barrier(0) after every
-  // MFMA slot keeps the compiler from regrouping it.  Tile kt is in LDS stage kt%2
-  // and registers ra/rb hold tile kt+1 on entry.  Each of the four 16-wide k steps
-  // issues 8 MFMAs on fragments that were read during the step before:
+  // MFMA slot keeps the compiler from regrouping it.  Tile kt is in LDS stage kt % 2 and
+  // the pieces of tile kt + 1 are in flight to the other stage on entry.  Each of the
+  // four 16-wide k steps issues 8 MFMAs on fragments that were read during the step before:
   //   step 0: MFMAs | fragment reads for step 1
   //   step 1: MFMAs | fragment reads for step 2
-  //   step 2: MFMAs | fragment reads for step 3, LDS writes of tile kt+1 (A), loads of tile kt+2 (A)
-  //   step 3: first 4 MFMAs | LDS writes of tile kt+1 (B), loads of tile kt+2 (B)
-  //           barrier; fragment reads for step 0 of tile kt+1; last 4 MFMAs
-  // so LDS latency is covered by MFMAs in flight (and by the SIMD's other
-  // wavefront), and a global load has a whole tile of MFMA time to land before its
-  // LDS write.  Past the last tile the loads are masked (zeros, no memory access)
-  // and the LDS writes are harmless, which keeps the loop body free of branches.
-  u32x4 ra[kPieces], rb[kPieces];
+  //   step 2: MFMAs | fragment reads for step 3
+  //   wait for this wavefront's pieces of tile kt + 1 and for its LDS reads; barrier:
+  //   now tile kt + 1 is complete and nobody reads the stage of tile kt any more
+  //   step 3: MFMAs | fragment reads for step 0 of tile kt + 1, and one piece of tile
+  //           kt + 2 per MFMA into the stage of tile kt
+  // so LDS latency is covered by MFMAs in flight (and by the SIMD's other wavefront), a
+  // piece has a whole k tile to land, and the memory instructions are spread out: a burst
+  // of them would hold up the wavefront's own MFMAs.  Past the last tile the loads are
+  // masked (zeros, no memory access), which keeps the loop body free of branches.
   bf16x8_t fa[2][2], fb[2][4];
   const uint32_t lda_b = (uint32_t)p.lda * 2, ldb_b = (uint32_t)p.ldb * 2;
   const bool gathered = MODE == MODE_GATEUP && p.gather != nullptr;
@@ -423,10 +485,19 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
                                : pieces_rowk(lda_b, t.m_end - t.m0, 256);
   const Pieces pb = B_TRANS ? pieces_krow(ldb_b, n_end - t.n0)
                             : pieces_rowk(ldb_b, n_end - t.n0, MODE == MODE_GATEUP ? 128 : 256);
+  const int wave_u = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  // the gate/up pairing: LDS rows 128..255 of operand B (the upper four wavefronts' pieces) come from the second matrix
+  const bool second_b = MODE == MODE_GATEUP && wave_u >= kWaves / 2;
+  // the 32-row blocks this wavefront reads: two of A, four of B (gate/up: two gate blocks and the two matching up blocks)
+  constexpr int kBlocksA[4] = {0, 1, 0, 0};
+  constexpr int kBlocksB[4] = {0, 1, MODE == MODE_GATEUP ? 4 : 2, MODE == MODE_GATEUP ? 5 : 3};
+  const FragAddr fra = frag_addr<A_TRANS>((wave_u >> 1) * 2, kBlocksA);
+  const FragAddr frb = frag_addr<B_TRANS>(MODE == MODE_GATEUP ? (wave_u & 1) * 2 : (wave_u & 1) * 4, kBlocksB);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)smem;  // LDS addresses are 32-bit offsets
 
-  // operand bases of k tile kt (wave-uniform), and how many k are left in it
+  // operand descriptors of k tile kt (wave-uniform), and how many k are left in it
   struct KTile {
-    rsrc_t a, b_lo, b_hi;
+    desc_t a, b;
     int k_left;
   };
   auto ktile = [&](int kt) {
@@ -436,26 +507,26 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     KTile q;
     q.k_left = kt < kt_hi ? k_end - k0 : 0;
     const bf16_t* A = ph == 0 ? p.A1 : p.A2;
-    const bf16_t* B = (MODE == MODE_DX && ph == 1) ? B2 : B1;
-    q.a = make_rsrc(A_TRANS ? A + (long)k0 * p.lda + t.m0 : A + (gathered ? 0 : (long)t.m0 * p.lda) + k0);
-    q.b_lo = make_rsrc(B_TRANS ? B + (long)k0 * p.ldb + t.n0 : B + (long)t.n0 * p.ldb + k0);
-    q.b_hi = MODE == MODE_GATEUP ? make_rsrc(B2 + (long)t.n0 * p.ldb + k0) : q.b_lo;
+    const bf16_t* B = ((MODE == MODE_DX && ph == 1) || second_b) ? B2 : B1;
+    q.a = make_desc(A_TRANS ? A + (long)k0 * p.lda + t.m0 : A + (gathered ? 0 : (long)t.m0 * p.lda) + k0, 0x7ffffffeu);
+    q.b = make_desc(B_TRANS ? B + (long)k0 * p.ldb + t.n0 : B + (long)t.n0 * p.ldb + k0, 0x7ffffffeu);
     return q;
   };
-  auto load_a = [&](const KTile& q, int j) { ra[j] = load_piece(q.a, pa, j, q.k_left); };
-  auto load_b = [&](const KTile& q, int j) {
-    rb[j] = load_piece((MODE == MODE_GATEUP && j >= kPieces / 2) ? q.b_hi : q.b_lo, pb, j, q.k_left);
+  // piece j of this wavefront, operand A / B of k tile q, into the stage at LDS offset `stage`
+  auto dma_a = [&](const KTile& q, uint32_t stage, int j) {
+    load_to_lds(q.a, stage + (wave_u * kPieces + j) * 1024, pa.kpos[j] < q.k_left ? pa.off[j] : kOob);
   };
-  // fragment f of a step: 0..1 = row blocks of A, 2..5 = column blocks of B
-  auto read_frag = [&](auto BUF, auto F, int stage, int ks) {
-    constexpr int Q = decltype(BUF)::value, f = decltype(F)::value;
-    const char* As = smem + (stage * 2) * kTileBytes;
+  auto dma_b = [&](const KTile& q, uint32_t stage, int j) {
+    load_to_lds(q.b, stage + kTileBytes + (wave_u * kPieces + j) * 1024, pb.kpos[j] < q.k_left ? pb.off[j] : kOob);
+  };
+  // fragment f of k step KS: 0..1 = row blocks of A, 2..5 = column blocks of B
+  auto read_frag = [&](auto BUF, auto F, const char* stage, auto KS) {
+    constexpr int Q = decltype(BUF)::value, f = decltype(F)::value, ks = decltype(KS)::value;
     if constexpr (f < 2) {
-      fa[Q][f] = lfrag<A_TRANS>(As, wm * 2 + f, ks);
+      fa[Q][f] = lfrag<A_TRANS, kBlocksA[f], ks>(stage, fra, f);
     } else {
       constexpr int j = f - 2;
-      const int blk = MODE == MODE_GATEUP ? (j >> 1) * 4 + wn * 2 + (j & 1) : wn * 4 + j;
-      fb[Q][j] = lfrag<B_TRANS>(As + kTileBytes, blk, ks);
+      fb[Q][j] = lfrag<B_TRANS, kBlocksB[j], ks>(stage + kTileBytes, frb, j);
     }
   };
   auto mfma = [&](auto BUF, auto M) {
@@ -464,90 +535,78 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   };
   const std::integral_constant<int, 0> c0;
   const std::integral_constant<int, 1> c1;
+  const std::integral_constant<int, 2> c2;
+  const std::integral_constant<int, 3> c3;
 
   {
     const KTile q0 = ktile(kt_lo);
-    static_for<kPieces>([&](auto J) { load_a(q0, J); });
-    static_for<kPieces>([&](auto J) { load_b(q0, J); });
-    static_for<kPieces>([&](auto J) { store_piece<A_TRANS>(smem, ra[J], J); });
-    static_for<kPieces>([&](auto J) { store_piece<B_TRANS>(smem + kTileBytes, rb[J], J); });
+    static_for<kPieces>([&](auto J) { dma_a(q0, lds0, J); });
+    static_for<kPieces>([&](auto J) { dma_b(q0, lds0, J); });
     const KTile q1 = ktile(kt_lo + 1);
-    static_for<kPieces>([&](auto J) { load_a(q1, J); });
-    static_for<kPieces>([&](auto J) { load_b(q1, J); });
+    static_for<kPieces>([&](auto J) { dma_a(q1, lds0 + kStageBytes, J); });
+    static_for<kPieces>([&](auto J) { dma_b(q1, lds0 + kStageBytes, J); });
   }
-  __syncthreads();
+  wait_loads_but<2 * kPieces>();  // the first tile has landed
+  wg_barrier();
   // A wavefront whose 64 x 128 part lies wholly outside the valid rows or columns (the
   // ragged last row tile of an expert, a narrow last column tile) only keeps up the
   // staging: it moves its pieces and meets the barriers, but reads no fragments and
   // issues no MFMAs, which leaves the SIMD and the LDS to the wavefronts that have work.
-  const int wave_u = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const bool has_work = t.m0 + (wave_u >> 1) * 64 < t.m_end &&
                         (MODE == MODE_GATEUP ? t.n0 + (wave_u & 1) * 64 : t.n0 + (wave_u & 1) * 128) < n_end;
   if (!has_work) {
     for (int kt = kt_lo; kt < kt_hi; ++kt) {
-      char* next = smem + ((((kt - kt_lo) & 1) ^ 1) * 2) * kTileBytes;
+      wait_loads_and_lds();
+      wg_barrier();
+      const uint32_t freed = lds0 + ((kt - kt_lo) & 1) * kStageBytes;
       const KTile q2 = ktile(kt + 2);
-      static_for<kPieces>([&](auto J) {
-        store_piece<A_TRANS>(next, ra[J], J);
-        load_a(q2, J);
-      });
-      static_for<kPieces>([&](auto J) {
-        store_piece<B_TRANS>(next + kTileBytes, rb[J], J);
-        load_b(q2, J);
-      });
-      __syncthreads();
+      static_for<kPieces>([&](auto J) { dma_a(q2, freed, J); });
+      static_for<kPieces>([&](auto J) { dma_b(q2, freed, J); });
     }
   } else {
-  static_for<6>([&](auto F) { read_frag(c0, F, 0, 0); });
+  static_for<6>([&](auto F) { read_frag(c0, F, smem, c0); });
 
   for (int kt = kt_lo; kt < kt_hi; ++kt) {
     const int stage = (kt - kt_lo) & 1;
-    char* next = smem + ((stage ^ 1) * 2) * kTileBytes;
+    const char* cur = smem + stage * kStageBytes;
+    const char* next = smem + (stage ^ 1) * kStageBytes;
+    const uint32_t freed = lds0 + stage * kStageBytes;
     const KTile q2 = ktile(kt + 2);
     __builtin_amdgcn_sched_barrier(0);
     // step 0: fragments of step 1 go to buffer 1
     static_for<8>([&](auto M) {
-      if constexpr (M < 6) read_frag(c1, M, stage, 1);
+      if constexpr (M < 6) read_frag(c1, M, cur, c1);
       mfma(c0, M);
       __builtin_amdgcn_sched_barrier(0);
     });
     // step 1
     static_for<8>([&](auto M) {
-      if constexpr (M < 6) read_frag(c0, M, stage, 2);
+      if constexpr (M < 6) read_frag(c0, M, cur, c2);
       mfma(c1, M);
       __builtin_amdgcn_sched_barrier(0);
     });
-    // step 2: also move operand A of the next tile into LDS and refill its registers
+    // step 2
     static_for<8>([&](auto M) {
-      if constexpr (M < 6) read_frag(c1, M, stage, 3);
-      if constexpr ((M & 1) == 1) {
-        store_piece<A_TRANS>(next, ra[M / 2], M / 2);
-        load_a(q2, M / 2);
-      }
+      if constexpr (M < 6) read_frag(c1, M, cur, c3);
       mfma(c0, M);
       __builtin_amdgcn_sched_barrier(0);
     });
-    // step 3, first half: operand B likewise
-    static_for<4>([&](auto M) {
-      store_piece<B_TRANS>(next + kTileBytes, rb[M], M);
-      load_b(q2, M);
-      mfma(c1, M);
-      __builtin_amdgcn_sched_barrier(0);
-    });
-    __syncthreads();
+    wait_loads_and_lds();
+    wg_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    // step 3, second half, with the next tile's first fragments in flight
-    static_for<4>([&](auto M) {
-      if constexpr (M < 3) {
-        read_frag(c0, std::integral_constant<int, 2 * M>{}, stage ^ 1, 0);
-        read_frag(c0, std::integral_constant<int, 2 * M + 1>{}, stage ^ 1, 0);
-      }
-      mfma(c1, std::integral_constant<int, M + 4>{});
+    // step 3: the next tile's first fragments, and the refill of the stage just freed
+    static_for<8>([&](auto M) {
+      if constexpr (M < 6) read_frag(c0, M, next, c0);
+      if constexpr (M < kPieces) dma_a(q2, freed, M);
+      else dma_b(q2, freed, M - kPieces);
+      mfma(c1, M);
       __builtin_amdgcn_sched_barrier(0);
     });
   }
   }  // has_work
-  __syncthreads();
+  // the stages become the epilogue's patches: every piece (masked ones included) has landed
+  wait_loads_and_lds();
+  wg_barrier();
 
   // ---- epilogue.  Accumulator element r of block (i, j) is row i*32 + (r/4)*8 +
   // (lane/32)*4 + r%4, column j*32 + lane%32 of the wavefront's 64x128 part.  Each
