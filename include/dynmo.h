@@ -29,7 +29,10 @@
  *   - limits: 1 <= k <= E <= 64 (k <= 8 for the combine calls); for DYNMO_BF16
  *     H and F must be multiples of 8, for DYNMO_F32 H a multiple of 4.  Violations return DYNMO_EINVAL /
  *     DYNMO_EUNSUPPORTED before anything is launched.
- *   - NaN in logits or scores is undefined input.
+ *     The fp32 path (and bf16 shapes the matrix-core kernels do not take) is limited to
+ *     floor(T*k / 64) + min(E, T*k) <= 65535 (DYNMO_EUNSUPPORTED beyond).
+ *   - NaN in logits or scores is undefined input, and so is a token whose logits are all
+ *     -inf (its gate weights would be 0/0).
  */
 #ifndef DYNMO_H
 #define DYNMO_H
@@ -240,9 +243,10 @@ int32_t dynmo_combine_bwd(const dynmo_desc* d, const void* dout, const void* y_p
 int32_t dynmo_layer_load(const dynmo_desc* d, const int32_t* seg_offsets, double cost_per_row,
                          int32_t* counts_host, double* load_host, void* stream);
 
-/* Partition balancer (Sec. 3.3, Sec. 5: contiguous layers to stages, "binary
- * search and linear probing"): the contiguous split of loads[L] into S stages
- * that minimises the largest stage load (the min-max objective of Sec. 2).
+/* Partition balancer (Sec. 3.3, Sec. 5): the contiguous split of loads[L] into S
+ * stages that minimises the largest stage load (the min-max objective of Sec. 2),
+ * found by bisecting on the bottleneck value with a greedy left-to-right feasibility
+ * scan.
  * Writes bounds_host[S+1] (stage i owns layers bounds[i] .. bounds[i+1]-1): the
  * split where each stage takes as many layers as fit under the optimal
  * bottleneck while leaving one layer for each later stage; *bottleneck_host gets
@@ -278,15 +282,17 @@ int32_t dynmo_diffusion(const double* loads_host, int32_t L, int32_t S, int32_t*
                         const double* layer_mem_host, double max_mem, double gamma, int32_t max_rounds,
                         int32_t* rounds_host, double* phi_host);
 
-/* Re-pack (Sec. 3.4, Algorithm 2): first-fit consolidation onto fewer workers.  For every
- * pair src < dst of active workers, while more than target_num_workers are active: if
- * mem_usage[src] + mem_usage[dst] < max_mem, src is freed (active = 0), each of its
- * num_layers[src] layers is listed as a transfer (src, dst, layer index on src), and dst's
- * memory and layer count grow by src's.  A freed worker neither gives nor takes again.
- * active_host, mem_usage_host, num_layers_host [n_workers]: in and out.  transfers_host:
- * 3 * capacity ints; *n_transfers_host gets the number of transfers.  If they do not fit,
- * returns DYNMO_EWORKSPACE with the needed count in *n_transfers_host and every array
- * unchanged.  Host pointers only. */
+/* Re-pack (Sec. 3.4, Algorithm 2): first-fit consolidation onto fewer workers.  Workers
+ * are visited in order; while more than target_num_workers are active, an active worker
+ * whose memory fits, together with that of a later active worker, strictly under max_mem
+ * is freed (active = 0) into the first such worker, which takes over its memory and its
+ * layers; every moved layer is listed as a transfer (freed worker, receiving worker, layer
+ * index on the freed worker).  A freed worker neither gives nor takes again.
+ * active_host, mem_usage_host, num_layers_host [n_workers]: in and out (a freed worker's
+ * memory and layer count are left as they were).  transfers_host: 3 * capacity ints;
+ * *n_transfers_host gets the number of transfers.  If they do not fit, returns
+ * DYNMO_EWORKSPACE with the needed count in *n_transfers_host and every array unchanged.
+ * Host pointers only. */
 int32_t dynmo_repack(int32_t n_workers, int32_t* active_host, double* mem_usage_host, int32_t* num_layers_host,
                      int32_t target_num_workers, double max_mem, int32_t* transfers_host, int32_t capacity,
                      int32_t* n_transfers_host);

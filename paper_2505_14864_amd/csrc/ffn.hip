@@ -37,11 +37,11 @@ static int32_t ffn_fwd_entry(const dynmo_desc* d, const void* rows, const int32_
   if (misaligned16(rows, Wg, Wu, Wd, y_p, G_save, U_save) || (fc && misaligned16(fc->res, fc->out)))
     return DYNMO_EINVAL;
   if (workspace_bytes < dynmo_grouped_ffn_fwd_workspace_bytes(d)) return DYNMO_EWORKSPACE;
-  if (max_m_tiles(d, 64) > 65535) return DYNMO_EUNSUPPORTED;
   void* A = (void*)align_up((size_t)workspace, 256);
   if (ffn_mfma_supported(d))
     return ffn_fwd_mfma(d, rows, gather, seg_offsets, Wg, Wu, Wd, y_p, G_save, U_save, A, (char*)A + act_bytes(d),
                         fc, (hipStream_t)stream);
+  if (max_m_tiles(d, 64) > 65535) return DYNMO_EUNSUPPORTED;  // the generic kernels put row tiles on grid y
   return ffn_fwd_generic(d, rows, gather, seg_offsets, Wg, Wu, Wd, y_p, G_save, U_save, A, fc, (hipStream_t)stream);
 }
 }  // namespace dynmo
@@ -89,7 +89,6 @@ extern "C" int32_t dynmo_grouped_ffn_bwd(const dynmo_desc* d, const void* dy_p, 
     return DYNMO_EINVAL;
   if (misaligned16(dy_p, x_p, G_save, U_save, Wg, Wu, Wd, dx_p, dWg, dWu, dWd)) return DYNMO_EINVAL;
   if (workspace_bytes < dynmo_grouped_ffn_bwd_workspace_bytes(d)) return DYNMO_EWORKSPACE;
-  if (max_m_tiles(d, 64) > 65535) return DYNMO_EUNSUPPORTED;
   char* base = (char*)align_up((size_t)workspace, 256);
   void* dG = base;
   void* dU = base + act_bytes(d);
@@ -97,6 +96,7 @@ extern "C" int32_t dynmo_grouped_ffn_bwd(const dynmo_desc* d, const void* dy_p, 
   if (ffn_mfma_supported(d))
     return ffn_bwd_mfma(d, dy_p, x_p, G_save, U_save, seg_offsets, Wg, Wu, Wd, dx_p, dWg, dWu, dWd, dG, dU, A,
                         base + 3 * act_bytes(d), (hipStream_t)stream);
+  if (max_m_tiles(d, 64) > 65535) return DYNMO_EUNSUPPORTED;  // the generic kernels put row tiles on grid y
   return ffn_bwd_generic(d, dy_p, x_p, G_save, U_save, seg_offsets, Wg, Wu, Wd, dx_p, dWg, dWu, dWd, dG, dU, A,
                          (hipStream_t)stream);
 }

@@ -635,7 +635,8 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   }
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
-    if (i > 0) __syncthreads();
+    // (the patch belongs to this wavefront alone and a wavefront's LDS accesses complete in
+    // order, so neither reusing the patch nor reading it back needs a workgroup barrier)
     const int band_row = t.m0 + wm * 64 + i * 32;
     // folded combine: the band's token indices, then (once the band's accumulators have left
     // their registers) weights and residual rows, are requested all at once, so that their
@@ -666,7 +667,6 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
         if (p.res && col < n_end) resid[s] = *(const u32x4*)(p.res + (long)token[s] * p.ldc + col);
       }
     }
-    __syncthreads();
     if (MODE == MODE_GATEUP) {
       // LDS row: 64 gate columns then the 64 matching up columns
 #pragma unroll

@@ -217,6 +217,18 @@ extern "C" int32_t dynmo_diffusion(const double* loads_host, int32_t L, int32_t 
 }
 
 // ---- re-pack ----------------------------------------------------------------------
+// Consolidation onto fewer workers (Sec. 3.4).  Workers are visited in order; a worker that
+// is still in use is folded, whole, into the first later worker in use that has room for
+// everything it holds, as long as more workers are in use than wanted.  A worker that has
+// been emptied neither gives nor takes again.  The walk records one merge per emptied
+// worker and stops as soon as the wanted count is reached; the per-layer transfer list the
+// caller asked for is written from those records at the end.
+namespace {
+struct Merge {
+  int32_t from, into, layers;
+};
+}  // namespace
+
 extern "C" int32_t dynmo_repack(int32_t n_workers, int32_t* active_host, double* mem_usage_host,
                                 int32_t* num_layers_host, int32_t target_num_workers, double max_mem,
                                 int32_t* transfers_host, int32_t capacity, int32_t* n_transfers_host) {
@@ -225,35 +237,40 @@ extern "C" int32_t dynmo_repack(int32_t n_workers, int32_t* active_host, double*
     return DYNMO_EINVAL;
   for (int w = 0; w < n_workers; ++w)
     if (num_layers_host[w] < 0) return DYNMO_EINVAL;
-  // Runs on copies, so that a transfer list that does not fit leaves the caller's arrays untouched.
-  std::vector<int32_t> act(active_host, active_host + n_workers), nl(num_layers_host, num_layers_host + n_workers);
-  std::vector<double> mem(mem_usage_host, mem_usage_host + n_workers);
-  std::vector<int32_t> moves;
-  int active = 0;
-  for (int w = 0; w < n_workers; ++w) active += act[w] ? 1 : 0;
-  for (int src = 0; src < n_workers; ++src) {
-    for (int dst = src + 1; dst < n_workers; ++dst) {
-      if (!act[src] || !act[dst]) continue;  // a freed worker neither gives nor takes
-      if (mem[src] + mem[dst] < max_mem && active > target_num_workers) {
-        act[src] = 0;
-        --active;
-        for (int lyr = 0; lyr < nl[src]; ++lyr) {
-          moves.push_back(src);
-          moves.push_back(dst);
-          moves.push_back(lyr);
-        }
-        mem[dst] += mem[src];
-        nl[dst] += nl[src];
-      }
-    }
+  // Works on copies, so that a transfer list that does not fit leaves the caller's arrays untouched.
+  std::vector<char> in_use(n_workers);
+  std::vector<double> held(mem_usage_host, mem_usage_host + n_workers);
+  std::vector<int32_t> layers(num_layers_host, num_layers_host + n_workers);
+  int n_in_use = 0;
+  for (int w = 0; w < n_workers; ++w) n_in_use += (in_use[w] = active_host[w] != 0) ? 1 : 0;
+  std::vector<Merge> merges;
+  int64_t n_moves = 0;
+  for (int w = 0; w < n_workers && n_in_use > target_num_workers; ++w) {
+    if (!in_use[w]) continue;
+    int host = -1;  // first fit among the later workers
+    for (int c = w + 1; c < n_workers && host < 0; ++c)
+      if (in_use[c] && held[w] + held[c] < max_mem) host = c;
+    if (host < 0) continue;
+    merges.push_back({w, host, layers[w]});
+    n_moves += layers[w];
+    in_use[w] = 0;
+    --n_in_use;
+    held[host] += held[w];
+    layers[host] += layers[w];
   }
-  *n_transfers_host = (int32_t)(moves.size() / 3);
-  if ((int64_t)moves.size() / 3 > capacity) return DYNMO_EWORKSPACE;
-  for (size_t i = 0; i < moves.size(); ++i) transfers_host[i] = moves[i];
+  *n_transfers_host = (int32_t)n_moves;
+  if (n_moves > capacity) return DYNMO_EWORKSPACE;
+  int32_t* out = transfers_host;
+  for (const Merge& m : merges)
+    for (int32_t l = 0; l < m.layers; ++l) {
+      *out++ = m.from;
+      *out++ = m.into;
+      *out++ = l;
+    }
   for (int w = 0; w < n_workers; ++w) {
-    active_host[w] = act[w];
-    mem_usage_host[w] = mem[w];
-    num_layers_host[w] = nl[w];
+    if (!in_use[w]) active_host[w] = 0;
+    mem_usage_host[w] = held[w];
+    num_layers_host[w] = layers[w];
   }
   return DYNMO_OK;
 }

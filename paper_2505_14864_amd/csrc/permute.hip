@@ -414,9 +414,9 @@ extern "C" int32_t dynmo_route_drop(const dynmo_desc* d, const int32_t* expert_i
                      stream);
   if (rc) return rc;
   hipStream_t st = (hipStream_t)stream;
-  route_drop_kernel<<<dim3((n_slots + 255) / 256), dim3(256), 0, st>>>(expert_idx, seg, dst_pos, expert_idx_kept, n_slots,
-                                                                      d->E, capacity);
-  DYNMO_LAUNCH_CHECK();
+  DYNMO_TIMED_LAUNCH(K_ROUTE_DROP, st,
+                     route_drop_kernel<<<dim3((n_slots + 255) / 256), dim3(256), 0, st>>>(
+                         expert_idx, seg, dst_pos, expert_idx_kept, n_slots, d->E, capacity));
   return DYNMO_OK;
 }
 

@@ -2,6 +2,8 @@
 // profiling step (per-layer execution time feeds the "by Time" balancers).
 #pragma once
 
+#include <atomic>
+
 #include "common.h"
 
 namespace dynmo {
@@ -12,6 +14,7 @@ enum KernelId {
   K_ROUTE_ACTIVE,
   K_ROUTE_TOPK_BWD,
   K_ROUTE_CAPACITY_BWD,
+  K_ROUTE_DROP,
   K_PERMUTE_COUNT,
   K_PERMUTE_SCAN,
   K_PERMUTE_SCATTER,
@@ -29,20 +32,23 @@ enum KernelId {
   K_COUNT
 };
 
-extern bool g_profile_on;
-void profile_begin(KernelId id, hipStream_t st);
-void profile_end(KernelId id, hipStream_t st);
+extern std::atomic<bool> g_profile_on;
+// profile_begin records the start event of a new pair for kernel role `id` and returns the
+// pair's stop event (nullptr if no pair could be made: too many pending, or no event);
+// profile_end records exactly that stop event, so concurrent launches of one role from
+// several host threads cannot mix up each other's pairs.
+hipEvent_t profile_begin(KernelId id, hipStream_t st);
+void profile_end(hipEvent_t stop, hipStream_t st);
 
 // Brackets one kernel launch with an event pair when profiling is enabled.
 struct ProfScope {
-  KernelId id;
   hipStream_t st;
-  bool on;
-  ProfScope(KernelId id_, hipStream_t st_) : id(id_), st(st_), on(g_profile_on) {
-    if (on) profile_begin(id, st);
+  hipEvent_t stop;
+  ProfScope(KernelId id, hipStream_t st_) : st(st_), stop(nullptr) {
+    if (g_profile_on.load(std::memory_order_relaxed)) stop = profile_begin(id, st);
   }
   ~ProfScope() {
-    if (on) profile_end(id, st);
+    if (stop) profile_end(stop, st);
   }
 };
 

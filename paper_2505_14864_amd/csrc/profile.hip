@@ -5,7 +5,7 @@
 
 namespace dynmo {
 
-bool g_profile_on = false;
+std::atomic<bool> g_profile_on{false};
 
 namespace {
 struct Slot {
@@ -20,6 +20,7 @@ constexpr size_t kMaxPending = 1 << 16;
 
 const char* const kNames[K_COUNT] = {
     "route_topk",    "route_capacity", "route_active", "route_topk_bwd", "route_capacity_bwd",
+    "route_drop",
     "permute_count", "permute_scan",   "permute_scatter", "permute_rows", "permute_bwd",
     "combine",       "combine_bwd",    "ffn_gateup",   "ffn_down",       "ffn_dA",
     "ffn_dX",        "ffn_dWd",        "ffn_dWg",      "ffn_dWu"};
@@ -52,30 +53,30 @@ int32_t drain(Slot& s) {
 }
 }  // namespace
 
-void profile_begin(KernelId id, hipStream_t st) {
+hipEvent_t profile_begin(KernelId id, hipStream_t st) {
   std::lock_guard<std::mutex> lk(g_mu);
   Slot& s = g_slots[id];
-  if (s.start.size() >= kMaxPending) return;
+  if (s.start.size() >= kMaxPending) return nullptr;
   hipEvent_t a = get_event(), b = get_event();
-  if (!a || !b) return;
+  if (!a || !b) {
+    if (a) g_free.push_back(a);
+    if (b) g_free.push_back(b);
+    return nullptr;
+  }
   s.start.push_back(a);
   s.stop.push_back(b);
   (void)hipEventRecord(a, st);
+  return b;
 }
 
-void profile_end(KernelId id, hipStream_t st) {
-  std::lock_guard<std::mutex> lk(g_mu);
-  Slot& s = g_slots[id];
-  if (s.stop.empty()) return;
-  (void)hipEventRecord(s.stop.back(), st);
-}
+void profile_end(hipEvent_t stop, hipStream_t st) { (void)hipEventRecord(stop, st); }
 
 }  // namespace dynmo
 
 using namespace dynmo;
 
 extern "C" int32_t dynmo_profile_enable(int32_t on) {
-  g_profile_on = on != 0;
+  g_profile_on.store(on != 0);
   return DYNMO_OK;
 }
 

@@ -1,5 +1,6 @@
-"""Shared helpers for the GPU parity tests: error metric, tolerances, and the
-sampled comparison used at sizes where the full oracle would take minutes."""
+"""Shared helpers for the GPU parity tests: error metrics, tolerances, the full
+element-by-element comparison and the sampled one (kept for the two configurations whose
+full oracle run does not fit the test budget)."""
 import numpy as np
 
 from oracle import dynmo_oracle as orc
@@ -11,6 +12,15 @@ from paper_2505_14864_amd.layer import to_host
 # (relative step 2^-8 = 3.9e-3); a few roundings in sequence stay below 2e-2.
 # fp32: dot products of length <= a few hundred in fp32 against fp64: ~1e-6.
 TOL = {"bf16": 2e-2, "f32": 1e-4}
+# Element-wise secondary measure |g - o| / (|o| + rms(o)).  The norm-wise measure divides by
+# max|o|, which is 4 to 5 rms(o) for these tensors; this one divides by about rms(o) at
+# elements near zero and is that much stricter there.  An element of a bf16 result is a sum
+# of terms that each carry about five independent roundings of relative size <= 2^-9
+# (standard deviation 2^-9 / sqrt(3) = 1.1e-3 each; the SwiGLU derivative amplifies those of
+# G by up to 2), so its error has a standard deviation of about 5e-3 rms(o); the largest of
+# up to 5e8 elements lies about 6.3 standard deviations out, 3.2e-2.  Bound: twice the
+# norm-wise tolerance.
+ELEMENT_TOL = {"bf16": 4e-2, "f32": 2e-4}
 
 
 def rel_err(got, ref):
@@ -29,6 +39,37 @@ def assert_close(name, got, ref, tol):
     e = rel_err(got, ref)
     assert e <= tol, "%s: max rel err %.3e > %.1e" % (name, e, tol)
     return e
+
+
+def group_rel_err(got, ref, bounds):
+    """Largest norm-wise error over groups of leading indices [bounds[g], bounds[g+1]): each
+    group is scaled by its own largest reference magnitude, so an error confined to a small
+    expert (or to the rows of one segment) is not hidden under the largest group's scale.
+    A group whose reference is all zero must be reproduced exactly."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    worst = 0.0
+    for g in range(len(bounds) - 1):
+        a, b = int(bounds[g]), int(bounds[g + 1])
+        if b <= a:
+            continue
+        scale = np.abs(ref[a:b]).max()
+        diff = np.abs(got[a:b] - ref[a:b]).max()
+        worst = max(worst, float(diff) if scale == 0.0 else float(diff / scale))
+    return worst
+
+
+def elementwise_excess(got, ref):
+    """The secondary, element-wise measure: max over elements of |g - o| / (|o| + rms(o))."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    if rms == 0.0:
+        return float(np.abs(got).max())
+    return float((np.abs(got - ref) / (np.abs(ref) + rms)).max())
 
 
 def sel(t, idx, dim=0):
@@ -134,11 +175,20 @@ def check_layer_sampled(layer, f, expert_idx_ref, gate_ref, residual, dtype, rng
     return dict(seg=seg, dst_pos=dst_pos, rows=rows, toks=toks)
 
 
-def check_layer_full(layer, ref, dtype, names=("y_p", "G", "U", "out", "dy_p", "dgate", "dx_p", "dx", "dWg", "dWu", "dWd")):
-    """Element-by-element comparison of every tensor with a full oracle run."""
+def check_layer_full(layer, ref, dtype, names=("y_p", "G", "U", "out", "dy_p", "dgate", "dx_p", "dx", "dWg", "dWu", "dWd"),
+                     assert_elementwise=False):
+    """Element-by-element comparison of every tensor with a full oracle run.
+
+    Three measures per tensor, all against the same tolerance: the norm-wise error over the
+    whole tensor; the same error with every expert's weight gradient and every expert's row
+    segment scaled on its own; and the element-wise |g - o| / (|o| + rms(o)), which is always
+    reported and, with assert_elementwise, held to ELEMENT_TOL (the benchmark configurations,
+    whose sums are long enough for that bound's derivation; an expert with a few dozen rows
+    has weight-gradient elements that are sums of a few dozen terms, with a heavier tail)."""
     tol = TOL[dtype]
-    R = int(ref["seg_offsets"][-1])
-    assert np.array_equal(to_host(layer.seg_offsets), ref["seg_offsets"])
+    seg = ref["seg_offsets"]
+    R = int(seg[-1])
+    assert np.array_equal(to_host(layer.seg_offsets), seg)
     assert np.array_equal(to_host(layer.dst_pos), ref["dst_pos"])
     assert np.array_equal(to_host(layer.src_slot)[:R], ref["src_slot"])
     assert np.array_equal(to_host(layer.x_p)[:R], np.asarray(ref["x_p"], dtype=np.float32))
@@ -148,4 +198,16 @@ def check_layer_full(layer, ref, dtype, names=("y_p", "G", "U", "out", "dy_p", "
         if n in ("y_p", "G", "U", "dy_p", "dx_p"):
             got = got[:R]
         errs[n] = assert_close(n, got, ref[n], tol)
+        if n in ("dWg", "dWu", "dWd"):
+            g = group_rel_err(got, ref[n], range(got.shape[0] + 1))
+            assert g <= tol, "%s: per-expert rel err %.3e > %.1e" % (n, g, tol)
+            errs[n + "/expert"] = g
+        elif n in ("y_p", "G", "U", "dy_p", "dx_p"):
+            g = group_rel_err(got, ref[n], seg)
+            assert g <= tol, "%s: per-segment rel err %.3e > %.1e" % (n, g, tol)
+            errs[n + "/segment"] = g
+        x = elementwise_excess(got, ref[n])
+        if assert_elementwise:
+            assert x <= ELEMENT_TOL[dtype], "%s: element-wise |g-o| / (|o| + rms) = %.3e > %.1e" % (n, x, ELEMENT_TOL[dtype])
+        errs[n + "/element"] = x
     return errs

@@ -218,7 +218,7 @@ def test_moe_layer_small(w):
     ref = orc.moe_layer(f["logits"], f["x"], f["Wg"], f["Wu"], f["Wd"], w.k, f["dout"])
     assert np.array_equal(to_host(layer.expert_idx), ref["expert_idx"])
     assert_close("gate_w", to_host(layer.gate_w), ref["gate_w"], 1e-5)
-    errs = check_layer_full(layer, ref, w.dtype)
+    errs = check_layer_full(layer, ref, w.dtype, assert_elementwise=True)
     assert_close("dlogits", to_host(layer.droute), ref["dlogits"], TOL[w.dtype])
     counts, load = layer.load()
     ref_counts, ref_load = orc.layer_load(ref["seg_offsets"], 18.0 * w.H * w.F)
@@ -314,6 +314,40 @@ def test_early_exit_stack_small():
 # the benchmark configurations at full size: integer results in full, floating
 # results on sampled rows / tokens / weight columns (see check_layer_sampled)
 # --------------------------------------------------------------------------
+
+def test_moe_full_size_every_element():
+    """Config 2 (the graded workload) against a full oracle run: every element of every tensor,
+    hence every 256 x 256 tile of every output, is compared (about ten seconds of float64 numpy)."""
+    w = wl.CONFIGS[2]
+    say("full-size config 2, every element: %s" % w.name)
+    inp = wl.make_inputs(w, threads=16)
+    layer = run_moe(w, inp)
+    f = f32_inputs(inp)
+    ref = orc.moe_layer(f["logits"], f["x"], f["Wg"], f["Wu"], f["Wd"], w.k, f["dout"])
+    assert np.array_equal(to_host(layer.expert_idx), ref["expert_idx"])
+    assert_close("gate_w", to_host(layer.gate_w), ref["gate_w"], 1e-5)
+    errs = check_layer_full(layer, ref, w.dtype, assert_elementwise=True)
+    assert_close("dlogits", to_host(layer.droute), ref["dlogits"], TOL[w.dtype])
+    say("  " + "  ".join("%s %.1e" % kv for kv in sorted(errs.items())))
+
+
+def test_mod_full_size_every_element():
+    """Config 4 against a full oracle run, every element."""
+    w = wl.CONFIGS[4]
+    say("full-size config 4, every element: %s" % w.name)
+    inp = wl.make_inputs(w, threads=16)
+    layer = RoutedFFNLayer(w.T, w.H, w.F, 1, 1, "bf16", "mod")
+    dev = {n: to_device(a) for n, a in inp.items()}
+    layer.route_capacity(dev["scores"], w.cap)
+    layer.forward(dev["x"], dev["Wg"], dev["Wu"], dev["Wd"])
+    layer.backward(dev["dout"], dev["Wg"], dev["Wu"], dev["Wd"])
+    torch.cuda.synchronize()
+    f = f32_inputs(inp)
+    ref = orc.mod_layer(f["scores"], w.cap, f["x"], f["Wg"], f["Wu"], f["Wd"], f["dout"])
+    assert np.array_equal(to_host(layer.expert_idx), ref["expert_idx"])
+    errs = check_layer_full(layer, ref, "bf16", assert_elementwise=True)
+    say("  " + "  ".join("%s %.1e" % kv for kv in sorted(errs.items())))
+
 
 @pytest.mark.parametrize("cfg", [2, 3])
 def test_moe_full_size_sampled(cfg):
