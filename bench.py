@@ -31,6 +31,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default 2: Mixtral-shaped MoE)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--print-kernel-sources-hash", action="store_true",
+                    help="print the hash of the kernel sources (recorded in the counter summaries under profiles/) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run one plain 1 GiB device copy (a known-size reference for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -79,23 +81,48 @@ def kernel_work(name, w, R_total, T):
     return table.get(name)
 
 
-def measured_traffic(config, kernel):
-    """HBM bytes per launch of `kernel` from the committed counter summary of this configuration (a table whose
-    rows are: kernel, read MB, written MB, total MB, ...), or None when no summary covers it."""
+def kernel_sources_hash():
+    """A short hash of the kernel sources (csrc/*.hip, *.h) the library is built from: counter summaries
+    under profiles/ record the hash they were taken on, and a figure is only quoted for the same code."""
     import glob
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2505_14864_amd", "csrc")
+    for path in sorted(glob.glob(os.path.join(csrc, "*.hip")) + glob.glob(os.path.join(csrc, "*.h"))):
+        h.update(os.path.basename(path).encode())
+        h.update(open(path, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(config, kernel):
+    """(bytes, stale): HBM bytes per launch of `kernel` from the committed counter summary of this
+    configuration (a table whose rows are: kernel, read MB, written MB, total MB, ...; a header line
+    `kernel sources: <hash>` names the code it was measured on).  bytes is None when no summary covers
+    the kernel, and also when the summary was taken on other kernel sources than the ones in the tree
+    (then stale is True): a counter figure is never quoted for code it was not measured on."""
+    import glob
+    current = kernel_sources_hash()
     for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "hbm_traffic_config%d_*.txt" % config))):
+        recorded, value = None, None
         for line in open(path):
             f = line.split()
+            if len(f) >= 3 and f[0] == "kernel" and f[1] == "sources:":
+                recorded = f[2]
             if len(f) >= 4 and f[0] in (kernel, kernel + "_kernel"):
                 try:
-                    return int(round(float(f[3]) * 1e6))
+                    value = int(round(float(f[3]) * 1e6))
                 except ValueError:
                     pass
-    return None
+        if value is not None:
+            return (value, False) if recorded == current else (None, True)
+    return None, False
 
 
 def main():
     a = parse()
+    if a.print_kernel_sources_hash:
+        print(kernel_sources_hash())
+        return
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); --gpus %d is not supported. "
               "value is the one GPU's throughput." % a.gpus, file=sys.stderr)
@@ -165,6 +192,9 @@ def main():
             B.dynmo_partition(per_task, stage_split)
         return rows, per_task
 
+    if a.reroute > 0 and w.mode == "mod":
+        print(json.dumps(reroute_mod_stack(a, w, dev)))
+        return
     if a.reroute > 0:
         print(json.dumps(reroute(a, w, dev, layers, Ws, step, stage_split)))
         return
@@ -221,11 +251,13 @@ def main():
         kernels.append(ent)
     kernels.sort(key=lambda e: -e["total_ms"])
     dom = next((e for e in kernels if "bound" in e), None)
-    traffic = measured_traffic(a.config, dom["name"]) if dom else None
+    traffic, traffic_stale = measured_traffic(a.config, dom["name"]) if dom else (None, False)
     roofline = None
     if dom:
         roofline = {"kernel": dom["name"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
                     "unit": dom["unit"], "frac": dom["frac"], "avg_us": dom["avg_us"], "traffic": traffic}
+        if traffic_stale:  # the committed counter summary was taken on other kernel sources
+            roofline["traffic_stale"] = True
 
     # imbalance of the exported load vector: equal-count split vs Partition
     imb = None
@@ -273,6 +305,72 @@ def main():
         "input_generation_s": round(gen_s, 1),
     }
     print(json.dumps(out))
+
+
+def reroute_mod_stack(a, w, dev, n_layers=8, S=4):
+    """Sec. 4 (Mixture of Depths): the routing wraps whole blocks, and a block that is skipped is
+    treated as a shadow layer when the layers are redistributed.  A stack of Mixture-of-Depths
+    blocks of this configuration's shape (all sharing one set of weights: only the cost matters
+    here); every iteration each block draws new router scores and its capacity from
+    {0, 0, 1/16, 1/8, 1/4} of the sequence, a capacity of zero being a skipped block.  The whole
+    stack runs forward and backward, the per-block loads are exported, and the stages are split
+    four ways: equal layer counts; Partition on the parameter loads (all blocks alike, so it
+    cannot see a skipped block); the same loads with the skipped blocks flagged as shadow layers;
+    Partition on the exported loads.  All four are judged by the exported (flop) loads."""
+    import torch
+    from paper_2505_14864_amd import binding as B
+    from paper_2505_14864_amd.layer import RoutedFFNLayer
+
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(w.seed)
+    layers = [RoutedFFNLayer(w.T, w.H, w.F, 1, 1, w.dtype, "mod") for _ in range(n_layers)]
+    for l in layers:
+        l.alloc_backward()
+    Ws = (dev["Wg"], dev["Wu"], dev["Wd"])
+    choices = [0, 0, w.S // 16, w.S // 8, w.S // 4]
+    param_loads = [3.0 * w.H * w.F] * n_layers
+    names = ("uniform", "partition_by_param", "partition_by_param_shadow", "partition_by_load")
+    rec = {n: [] for n in names}
+    most = {"partition_by_load": [], "partition_by_param_shadow": []}
+    shadow_count, t_step = [], []
+    for it in range(max(1, a.warmup) + a.reroute):
+        pick = torch.randint(0, len(choices), (n_layers,), generator=gen, device="cuda").tolist()
+        caps = [choices[i] for i in pick]
+        scores = [torch.randn(w.B, w.S, generator=gen, device="cuda") for _ in range(n_layers)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        x = dev["x"]
+        for l, layer in enumerate(layers):
+            layer.route_capacity(scores[l], caps[l])
+            x = layer.forward(x, *Ws)
+        g = dev["dout"]
+        for l in range(n_layers - 1, -1, -1):
+            g = layers[l].backward(g, *Ws)
+            layers[l].route_bwd(scores[l])
+        loads = [layer.load()[1] for layer in layers]  # device -> host, synchronises
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        if it < max(1, a.warmup) or sum(loads) <= 0:
+            continue
+        shadow = [1 if c == 0 else 0 for c in caps]
+        splits = {
+            "uniform": B.dynmo_uniform_bounds(n_layers, S),
+            "partition_by_param": B.dynmo_partition(param_loads, S)[0],
+            "partition_by_param_shadow": B.dynmo_partition_shadow(param_loads, shadow, S)[0],
+            "partition_by_load": B.dynmo_partition(loads, S)[0],
+        }
+        for n, b in splits.items():
+            rec[n].append(round(B.dynmo_imbalance(B.dynmo_stage_loads(loads, b)), 4))
+        for n in most:
+            most[n].append(max(splits[n][i + 1] - splits[n][i] for i in range(S)))
+        shadow_count.append(sum(shadow))
+        t_step.append(t1 - t0)
+    mean = lambda xs: sum(xs) / max(1, len(xs))
+    return {"workload": "config %d: %s, a stack of %d blocks" % (a.config, w.name, n_layers), "iterations": a.reroute,
+            "stages": S, "tasks": "layers", "capacities": choices, "mean_shadow_layers": round(mean(shadow_count), 2),
+            "imbalance": rec, "mean_imbalance": {k: round(mean(v), 4) for k, v in rec.items()},
+            "mean_most_layers_on_a_stage": {k: round(mean(v), 2) for k, v in most.items()},
+            "ms_per_iteration": round(1e3 * mean(t_step), 4)}
 
 
 def reroute(a, w, dev, layers, Ws, step, S):

@@ -254,6 +254,18 @@ int32_t dynmo_layer_load(const dynmo_desc* d, const int32_t* seg_offsets, double
 int32_t dynmo_partition(const double* loads_host, int32_t L, int32_t S, int32_t* bounds_host,
                         double* bottleneck_host);
 
+/* Partition with shadow layers (Sec. 4, Mixture of Depths: a block that is skipped is treated
+ * as a shadow layer when the layers are redistributed).  shadow_host [L] (NULL = none): a
+ * non-zero entry marks a layer that keeps its place in the order and its memory but adds no
+ * load.  The split minimises first the largest stage load, with the shadow layers counted as
+ * zero, and then, among the splits that reach that optimum, the largest number of layers on
+ * one stage (free layers are spread instead of piling up on one worker).  bounds_host [S+1]:
+ * from the left, each stage takes as many layers as both limits allow while leaving one layer
+ * for every later stage; *bottleneck_host and *max_layers_host get the two optima.  Host
+ * pointers only; loads must be finite and >= 0. */
+int32_t dynmo_partition_shadow(const double* loads_host, const int32_t* shadow_host, int32_t L, int32_t S,
+                               int32_t* bounds_host, double* bottleneck_host, int32_t* max_layers_host);
+
 /* Equal layer counts per stage (the static split the paper compares against). */
 int32_t dynmo_uniform_bounds(int32_t L, int32_t S, int32_t* bounds_host);
 

@@ -476,6 +476,64 @@ def partition_canonical_bounds(loads, S, bottleneck):
     return np.asarray(bounds, dtype=I32)
 
 
+def partition_shadow(loads, shadow, S):
+    """Partition with shadow layers (Sec. 4, Mixture of Depths: a block that is skipped is
+    treated as a shadow layer when the layers are redistributed over the workers).
+
+    Reading taken (the paper names the idea only): a shadow layer keeps its place in the
+    layer order and its memory but adds no load.  A contiguous split is therefore judged
+    first by its bottleneck max_i L_i, computed with the shadow layers' loads set to zero
+    (the objective of Sec. 2), and among the splits that reach the optimal bottleneck by
+    the largest number of layers any stage has to hold -- free layers can sit on either
+    side of a boundary, so they are spread instead of piling up on one worker.  Stages are
+    non-empty when L >= S.  Of the splits optimal in both, the canonical one lets each stage,
+    from the left, take as many layers as both limits allow while leaving one layer for
+    every later stage.
+
+    Two exact dynamic programs over prefix sums, the second restricted to stages whose
+    load stays under the first one's optimum:
+      best[s][j]  = min_i max(best[s-1][i],  prefix[j] - prefix[i])
+      count[s][j] = min_i max(count[s-1][i], j - i)   over i with prefix[j] - prefix[i] <= bottleneck
+    Returns (bottleneck, max_layers, bounds int32 [S+1]).
+    """
+    loads = _f64(loads)
+    L = loads.size
+    eff = [0.0 if (shadow is not None and shadow[i]) else float(loads[i]) for i in range(L)]
+    bottleneck = partition_dp(eff, S)
+    prefix = [0.0] * (L + 1)
+    for i in range(L):
+        prefix[i + 1] = prefix[i] + eff[i]
+    INF = float("inf")
+    need_nonempty = L >= S
+    count = [[INF] * (L + 1) for _ in range(S + 1)]
+    count[0][0] = 0
+    for s in range(1, S + 1):
+        for j in range(0, L + 1):
+            b = INF
+            for i in range(0, j + 1):
+                if count[s - 1][i] == INF or (need_nonempty and i == j):
+                    continue
+                if prefix[j] - prefix[i] <= bottleneck:
+                    b = min(b, max(count[s - 1][i], j - i))
+            count[s][j] = b
+    max_layers = int(count[S][L])
+    bounds = [0]
+    start = 0
+    for s in range(S):
+        if s == S - 1:
+            end = L
+        else:
+            limit = L - (S - s - 1) if need_nonempty else L
+            end = start
+            while end < limit and end - start < max_layers and prefix[end + 1] - prefix[start] <= bottleneck:
+                end += 1
+            if need_nonempty and end == start:
+                end = start + 1
+        bounds.append(end)
+        start = end
+    return bottleneck, max_layers, np.asarray(bounds, dtype=I32)
+
+
 def uniform_bounds(L, S):
     """The static baseline the paper compares against: equal layer counts per
     stage (remainder to the first stages)."""

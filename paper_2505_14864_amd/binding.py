@@ -65,6 +65,8 @@ SIGNATURES = {
     "dynmo_combine_bwd": (_I, [_D, _P, _P, _P, _P, _P, _P, _P]),
     "dynmo_layer_load": (_I, [_D, _P, C.c_double, C.POINTER(C.c_int32), C.POINTER(C.c_double), _P]),
     "dynmo_partition": (_I, [C.POINTER(C.c_double), _I, _I, C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
+    "dynmo_partition_shadow": (_I, [C.POINTER(C.c_double), C.POINTER(C.c_int32), _I, _I, C.POINTER(C.c_int32),
+                                    C.POINTER(C.c_double), C.POINTER(C.c_int32)]),
     "dynmo_uniform_bounds": (_I, [_I, _I, C.POINTER(C.c_int32)]),
     "dynmo_stage_loads": (_I, [C.POINTER(C.c_double), _I, C.POINTER(C.c_int32), _I, C.POINTER(C.c_double)]),
     "dynmo_imbalance": (_I, [C.POINTER(C.c_double), _I, C.POINTER(C.c_double)]),
@@ -269,6 +271,17 @@ def dynmo_partition(loads, S):
     b = C.c_double()
     _check("dynmo_partition", lib().dynmo_partition(_darr(loads), len(loads), S, bounds, C.byref(b)))
     return list(bounds), b.value
+
+
+def dynmo_partition_shadow(loads, shadow, S):
+    """Returns (bounds list[S+1], bottleneck, most layers on one stage)."""
+    bounds = (C.c_int32 * (S + 1))()
+    b = C.c_double()
+    m = C.c_int32()
+    sh = None if shadow is None else (C.c_int32 * len(loads))(*[int(v) for v in shadow])
+    _check("dynmo_partition_shadow", lib().dynmo_partition_shadow(_darr(loads), sh, len(loads), S, bounds, C.byref(b),
+                                                                  C.byref(m)))
+    return list(bounds), b.value, m.value
 
 
 def dynmo_uniform_bounds(L, S):

@@ -38,18 +38,62 @@ struct Prefix {
 };
 
 // Linear probe: can the layers be covered by at most S contiguous stages whose
-// sums do not exceed `cap`?  Greedy left to right.
-bool feasible(const Prefix& pre, int L, int S, double cap) {
+// sums do not exceed `cap` and that hold at most `max_layers` layers each?  Greedy left to right.
+bool feasible(const Prefix& pre, int L, int S, double cap, int max_layers = 1 << 30) {
   int start = 0, used = 0;
   while (start < L) {
     if (used == S) return false;
     int end = start;
-    while (end < L && pre.sum(start, end + 1) <= cap) ++end;
+    while (end < L && end - start < max_layers && pre.sum(start, end + 1) <= cap) ++end;
     if (end == start) return false;  // a single layer exceeds cap
     start = end;
     ++used;
   }
   return true;
+}
+
+// Binary search on the bottleneck value.  Feasibility is monotone in the cap,
+// and the optimum is itself a double (some prefix difference), so bisecting
+// down to adjacent doubles lands exactly on it.
+double optimal_bottleneck(const Prefix& pre, const double* loads, int L, int S) {
+  double lo = 0.0;  // lo is infeasible unless it is the answer
+  for (int i = 0; i < L; ++i) lo = fmax(lo, loads[i]);
+  double hi = pre.sum(0, L);
+  if (hi < lo) hi = lo;
+  if (L == 0 || feasible(pre, L, S, lo)) return lo;
+  while (true) {
+    const double mid = lo + (hi - lo) * 0.5;
+    if (!(mid > lo) || !(mid < hi)) break;
+    if (feasible(pre, L, S, mid))
+      hi = mid;
+    else
+      lo = mid;
+  }
+  return hi;
+}
+
+// The split: each stage takes as many layers as fit under both limits, but leaves one layer
+// for every later stage (when there are at least as many layers as stages).  Returns the
+// largest stage sum of the split.
+double greedy_bounds(const Prefix& pre, int L, int S, double cap, int max_layers, int32_t* bounds) {
+  int start = 0;
+  bounds[0] = 0;
+  double realised = 0.0;
+  for (int s = 0; s < S; ++s) {
+    int end;
+    if (s == S - 1) {
+      end = L;
+    } else {
+      const int limit = L >= S ? L - (S - s - 1) : L;
+      end = start;
+      while (end < limit && end - start < max_layers && pre.sum(start, end + 1) <= cap) ++end;
+      if (L >= S && end == start) end = start + 1;
+    }
+    realised = fmax(realised, pre.sum(start, end));
+    bounds[s + 1] = end;
+    start = end;
+  }
+  return realised;
 }
 
 }  // namespace
@@ -60,47 +104,37 @@ extern "C" int32_t dynmo_partition(const double* loads_host, int32_t L, int32_t 
   for (int i = 0; i < L; ++i)
     if (!(loads_host[i] >= 0.0) || !isfinite(loads_host[i])) return DYNMO_EINVAL;
   Prefix pre(loads_host, L);
-  // Binary search on the bottleneck value.  Feasibility is monotone in the cap,
-  // and the optimum is itself a double (some prefix difference), so bisecting
-  // down to adjacent doubles lands exactly on it.
-  double lo = 0.0;  // lo is infeasible unless it is the answer
-  for (int i = 0; i < L; ++i) lo = fmax(lo, loads_host[i]);
-  double hi = pre.sum(0, L);
-  if (hi < lo) hi = lo;
-  double best = hi;
-  if (L == 0 || feasible(pre, L, S, lo)) {
-    best = lo;
-  } else {
-    while (true) {
-      const double mid = lo + (hi - lo) * 0.5;
-      if (!(mid > lo) || !(mid < hi)) break;
-      if (feasible(pre, L, S, mid))
-        hi = mid;
-      else
-        lo = mid;
-    }
-    best = hi;
+  const double best = optimal_bottleneck(pre, loads_host, L, S);
+  *bottleneck_host = greedy_bounds(pre, L, S, best, 1 << 30, bounds_host);
+  return DYNMO_OK;
+}
+
+extern "C" int32_t dynmo_partition_shadow(const double* loads_host, const int32_t* shadow_host, int32_t L, int32_t S,
+                                          int32_t* bounds_host, double* bottleneck_host, int32_t* max_layers_host) {
+  if (!loads_host || !bounds_host || !bottleneck_host || !max_layers_host || L < 0 || S <= 0) return DYNMO_EINVAL;
+  for (int i = 0; i < L; ++i)
+    if (!(loads_host[i] >= 0.0) || !isfinite(loads_host[i])) return DYNMO_EINVAL;
+  // a shadow layer keeps its place and its memory but adds no load
+  std::vector<double> eff(loads_host, loads_host + L);
+  if (shadow_host)
+    for (int i = 0; i < L; ++i)
+      if (shadow_host[i]) eff[i] = 0.0;
+  Prefix pre(eff.data(), L);
+  const double best = optimal_bottleneck(pre, eff.data(), L, S);
+  // Second criterion: the fewest layers on the fullest stage among the splits that keep the
+  // optimal bottleneck.  Feasibility is monotone in that count too.
+  int lo = L == 0 ? 0 : (L + S - 1) / S, hi = L;  // lo may be infeasible, hi is feasible
+  while (lo < hi) {
+    const int mid = lo + (hi - lo) / 2;
+    if (feasible(pre, L, S, best, mid))
+      hi = mid;
+    else
+      lo = mid + 1;
   }
-  // The split: each stage takes as many layers as fit, but leaves one layer for
-  // every later stage (when there are at least as many layers as stages).
-  int start = 0;
-  bounds_host[0] = 0;
-  double realised = 0.0;
-  for (int s = 0; s < S; ++s) {
-    int end;
-    if (s == S - 1) {
-      end = L;
-    } else {
-      const int limit = L >= S ? L - (S - s - 1) : L;
-      end = start;
-      while (end < limit && pre.sum(start, end + 1) <= best) ++end;
-      if (L >= S && end == start) end = start + 1;
-    }
-    realised = fmax(realised, pre.sum(start, end));
-    bounds_host[s + 1] = end;
-    start = end;
-  }
-  *bottleneck_host = realised;
+  *bottleneck_host = greedy_bounds(pre, L, S, best, hi, bounds_host);
+  int most = 0;
+  for (int s = 0; s < S; ++s) most = bounds_host[s + 1] - bounds_host[s] > most ? bounds_host[s + 1] - bounds_host[s] : most;
+  *max_layers_host = most;
   return DYNMO_OK;
 }
 

@@ -267,21 +267,84 @@ def test_product_and_oracle_do_not_import_each_other():
         assert word not in src, word
 
 
-def test_bench_reads_measured_traffic_from_the_committed_summary():
-    """roofline.traffic comes from the counter summary under profiles/: the table must parse, give
-    at least the kernel's algorithmic bytes, and give nothing for a kernel or configuration it lacks."""
+def _load_bench():
     import importlib.util
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     spec = importlib.util.spec_from_file_location("bench_mod2", os.path.join(root, "bench.py"))
     bench = importlib.util.module_from_spec(spec)
     spec.loader.exec_module(bench)
+    return bench
+
+
+def test_bench_quotes_measured_traffic_only_for_the_code_it_was_measured_on(tmp_path, monkeypatch):
+    """roofline.traffic comes from a counter summary under profiles/ that records the hash of the kernel
+    sources it was taken on: the table must parse and give at least the kernel's algorithmic bytes when
+    the hash matches the tree, give (None, stale) when it does not, and nothing for a kernel or
+    configuration it lacks."""
+    bench = _load_bench()
     from paper_2505_14864_amd import workloads as wl
     w = wl.CONFIGS[2]
     R = w.T * w.k
-    for name in ("ffn_dX", "ffn_gateup", "ffn_down", "ffn_dA"):
-        got = bench.measured_traffic(2, name)
-        assert got is not None and got > 1e9, name
-    rows_moved = bench.measured_traffic(2, "permute_rows")
-    assert rows_moved is not None and abs(rows_moved - bench.kernel_work("permute_rows", w, R, w.T)[1]) < 0.02 * rows_moved
-    assert bench.measured_traffic(2, "no_such_kernel") is None
-    assert bench.measured_traffic(1, "ffn_dX") is None
+    prof = tmp_path / "profiles"
+    prof.mkdir()
+    table = ("kernel                            read MB   written MB     total MB algorithmic MB    ratio\n"
+             "ffn_dX                             4970.5        126.7       5097.3         2415.9     2.11\n"
+             "permute_rows_kernel                  33.7         67.1        100.8          100.7     1.00\n")
+    monkeypatch.setattr(bench, "ROOT", str(tmp_path))
+    monkeypatch.setattr(bench, "kernel_sources_hash", lambda: "0123456789abcdef")
+    (prof / "hbm_traffic_config2_x.txt").write_text("header\nkernel sources: 0123456789abcdef\n\n" + table)
+    assert bench.measured_traffic(2, "ffn_dX") == (5097300000, False)
+    rows_moved, stale = bench.measured_traffic(2, "permute_rows")
+    assert not stale and abs(rows_moved - bench.kernel_work("permute_rows", w, R, w.T)[1]) < 0.02 * rows_moved
+    assert bench.measured_traffic(2, "no_such_kernel") == (None, False)
+    assert bench.measured_traffic(1, "ffn_dX") == (None, False)
+    # the same summary after the kernels have changed, and one that records no hash at all
+    monkeypatch.setattr(bench, "kernel_sources_hash", lambda: "fedcba9876543210")
+    assert bench.measured_traffic(2, "ffn_dX") == (None, True)
+    (prof / "hbm_traffic_config2_x.txt").write_text("header\n\n" + table)
+    assert bench.measured_traffic(2, "ffn_dX") == (None, True)
+
+
+def test_kernel_sources_hash_follows_the_sources(tmp_path, monkeypatch):
+    bench = _load_bench()
+    real = bench.kernel_sources_hash()
+    assert len(real) == 16 and real == bench.kernel_sources_hash()
+    csrc = tmp_path / "paper_2505_14864_amd" / "csrc"
+    csrc.mkdir(parents=True)
+    (csrc / "a.hip").write_text("one")
+    monkeypatch.setattr(bench, "ROOT", str(tmp_path))
+    h1 = bench.kernel_sources_hash()
+    (csrc / "a.hip").write_text("two")
+    assert bench.kernel_sources_hash() != h1
+
+
+def test_committed_traffic_summaries_name_their_sources():
+    """Every committed HBM-traffic summary carries the `kernel sources:` line the bench checks."""
+    import glob
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    for path in glob.glob(os.path.join(root, "profiles", "hbm_traffic_*.txt")):
+        assert any(l.startswith("kernel sources: ") for l in open(path)), path
+
+
+def test_partition_shadow_matches_oracle():
+    """The library's shadow-layer split against the oracle's two dynamic programs (themselves
+    pinned by enumeration and hand-worked cases), on random loads, shadow sets and stage counts."""
+    rng = np.random.default_rng(5)
+    for trial in range(200):
+        L = int(rng.integers(0, 40))
+        S = int(rng.integers(1, 9))
+        integral = trial % 2 == 0
+        loads = rng.integers(0, 50, size=L).astype(float) if integral else rng.random(L) * 10
+        shadow = (rng.random(L) < rng.random()).astype(int)
+        if L == 0:
+            bounds, bott, most = B.dynmo_partition_shadow(loads, shadow, S)
+            assert bounds == [0] * (S + 1) and bott == 0.0 and most == 0
+            continue
+        bounds, bott, most = B.dynmo_partition_shadow(loads, shadow, S)
+        ref_b, ref_m, ref_bounds = orc.partition_shadow(loads, shadow, S)
+        assert bott == ref_b and most == ref_m and bounds == list(ref_bounds), (loads, shadow, S)
+    # no shadow flags: the Partition balancer's bottleneck
+    loads = [7.0, 2.0, 5.0, 10.0, 8.0]
+    assert B.dynmo_partition_shadow(loads, None, 3)[1] == B.dynmo_partition(loads, 3)[1] == 14.0
+    with pytest.raises(B.DynmoError):
+        B.dynmo_partition_shadow([1.0, float("nan")], [0, 0], 2)

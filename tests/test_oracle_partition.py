@@ -167,3 +167,65 @@ def test_diffusion_respects_memory():
     free, _ = orc.diffusion_balance(loads, [0, 3, 6])
     assert list(free) == [0, 1, 6]          # 9 | 5 without the cap
     assert list(b) == [0, 2, 6]             # 10 | 4: stage 1 may hold four layers at most
+
+
+# --------------------------------------------------------------------------
+# shadow layers (Sec. 4, Mixture of Depths)
+# --------------------------------------------------------------------------
+
+def _shadow_bruteforce(loads, shadow, S):
+    """All contiguous splits into S non-empty stages, judged by (bottleneck, most layers on a
+    stage), ties by the lexicographically largest bounds (= every stage takes all it can)."""
+    import itertools
+    L = len(loads)
+    eff = [0.0 if shadow[i] else float(loads[i]) for i in range(L)]
+    best = None
+    for cuts in itertools.combinations(range(1, L), S - 1):
+        b = (0,) + cuts + (L,)
+        sums = [sum(eff[b[s]:b[s + 1]]) for s in range(S)]
+        key = (max(sums), max(b[s + 1] - b[s] for s in range(S)), tuple(-v for v in b))
+        if best is None or key < best[0]:
+            best = (key, b)
+    return best[0][0], best[0][1], list(best[1])
+
+
+def test_partition_shadow_hand_values(golden_dir):
+    n = 0
+    for line in open(os.path.join(golden_dir, "partition_shadow_hand.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        S, bott, most, bounds, loads, shadow = [f.strip() for f in line.split("|")]
+        loads = [float(v) for v in loads.split()]
+        shadow = [int(v) for v in shadow.split()]
+        got = orc.partition_shadow(loads, shadow, int(S))
+        assert got[0] == float(bott) and got[1] == int(most), line
+        assert list(got[2]) == [int(v) for v in bounds.split()], line
+        n += 1
+    assert n >= 5
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_partition_shadow_equals_enumeration(seed):
+    rng = np.random.default_rng(100 + seed)
+    for _ in range(40):
+        L = int(rng.integers(2, 11))
+        S = int(rng.integers(1, L + 1))
+        loads = rng.integers(0, 9, size=L).astype(float)
+        shadow = (rng.random(L) < 0.4).astype(int)
+        bott, most, bounds = orc.partition_shadow(loads, shadow, S)
+        ref = _shadow_bruteforce(loads, shadow, S)
+        assert (bott, most, list(bounds)) == ref, (loads, shadow, S)
+
+
+def test_partition_shadow_reduces_to_partition():
+    # with no shadow layer the bottleneck is the Partition balancer's, and flagging a layer as
+    # shadow can only lower it
+    rng = np.random.default_rng(7)
+    for _ in range(30):
+        L = int(rng.integers(3, 12))
+        S = int(rng.integers(1, L + 1))
+        loads = rng.integers(1, 20, size=L).astype(float)
+        none = np.zeros(L, int)
+        assert orc.partition_shadow(loads, none, S)[0] == orc.partition_dp(loads, S)
+        some = (rng.random(L) < 0.5).astype(int)
+        assert orc.partition_shadow(loads, some, S)[0] <= orc.partition_dp(loads, S)
