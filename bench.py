@@ -38,7 +38,8 @@ def parse():
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--folded-combine", action="store_true",
                     help="configurations with one slot per token (4, 5): fold the combine into the last product "
-                         "(dynmo_grouped_ffn_fwd_combine) instead of the separate dynmo_combine pass")
+                         "(dynmo_grouped_ffn_fwd_combine) and the scatter back to token order into the dX product "
+                         "(dynmo_grouped_ffn_bwd_scatter) instead of the separate dynmo_combine / dynmo_permute_bwd passes")
     ap.add_argument("--reroute", type=int, default=0, metavar="N",
                     help="instead of the headline line: N iterations with fresh router inputs each (the routing "
                          "decision changes every iteration), the exported loads rebalanced every iteration; prints "
@@ -155,6 +156,7 @@ def main():
         print("bench.py: --folded-combine needs a configuration with one slot per token (4 or 5)", file=sys.stderr)
         sys.exit(2)
     primed = []
+    primed_bwd = []
 
     def step():
         """One pass of the hot path; returns (routed rows, loads for the balancer)."""
@@ -177,7 +179,15 @@ def main():
                 x = layer.forward(x, *Ws[i])
         g = dev["dout"]
         for i in range(L - 1, -1, -1):
-            g = layers[i].backward(g, *Ws[i])
+            if a.folded_combine:
+                # as in the forward pass: the gradient rows of unrouted tokens are not rewritten, and every
+                # step sees the same routing and the same upstream gradient, so they are given once
+                if len(primed_bwd) < L:
+                    layers[i].dx.copy_(g)
+                    primed_bwd.append(i)
+                g = layers[i].backward_folded(g, *Ws[i], dx=layers[i].dx)
+            else:
+                g = layers[i].backward(g, *Ws[i])
             if w.mode == "moe":
                 layers[i].route_bwd()
             elif w.mode == "mod":
@@ -593,7 +603,15 @@ def protocol(a, w, inp, dev, layers, Ws, step):
         fwd_only()
         g = dev["dout"]
         for i in range(L - 1, -1, -1):
-            g = layers[i].backward(g, *Ws[i])
+            if a.folded_combine:
+                # as in the forward pass: the gradient rows of unrouted tokens are not rewritten, and every
+                # step sees the same routing and the same upstream gradient, so they are given once
+                if len(primed_bwd) < L:
+                    layers[i].dx.copy_(g)
+                    primed_bwd.append(i)
+                g = layers[i].backward_folded(g, *Ws[i], dx=layers[i].dx)
+            else:
+                g = layers[i].backward(g, *Ws[i])
             if w.mode == "moe":
                 layers[i].route_bwd()
             elif w.mode == "mod":

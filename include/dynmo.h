@@ -219,6 +219,21 @@ int32_t dynmo_grouped_ffn_bwd(const dynmo_desc* d, const void* dy_p, const void*
                               const void* Wd, void* dx_p, void* dWg, void* dWu, void* dWd, void* workspace,
                               size_t workspace_bytes, void* stream);
 
+/* The backward pass for k = 1 (Mixture-of-Depths, Sec. 2.6; the shrinking layers of Sec. 2.5;
+ * top-1 MoE) with the scatter back to token order (dynmo_permute_bwd) folded into the stores of
+ * the dX product: for every routed row p, with t = src_slot[p],  dx[t] = dbase[t] + dX[p]
+ * (fp32 sum, rounded once).  Rows of dx whose token has no routed row are NOT written: with
+ * dbase == dx the upstream gradient of the residual stream is updated in place and unrouted
+ * tokens pass through at no traffic; with dbase == NULL (zero) or a separate dbase the caller
+ * owns those rows.  dx_p [T,H] or NULL (the rows in expert order, if the caller wants them);
+ * everything else, and the workspace size, as for dynmo_grouped_ffn_bwd.  d->k != 1 gives
+ * DYNMO_EINVAL. */
+int32_t dynmo_grouped_ffn_bwd_scatter(const dynmo_desc* d, const void* dy_p, const void* x_p, const void* G_save,
+                                      const void* U_save, const int32_t* seg_offsets, const int32_t* src_slot,
+                                      const void* Wg, const void* Wu, const void* Wd, const void* dbase, void* dx,
+                                      void* dx_p, void* dWg, void* dWu, void* dWd, void* workspace,
+                                      size_t workspace_bytes, void* stream);
+
 /* ---- combine ----------------------------------------------------------- */
 
 /* out[t] = base[t] + sum over routed slots s (ascending) of gate_w[t,s] y_p[dst_pos[t,s]].

@@ -61,6 +61,7 @@ SIGNATURES = {
     "dynmo_grouped_ffn_fwd_combine": (_I, [_D] + [_P] * 14 + [C.c_size_t, _P]),
     "dynmo_grouped_ffn_bwd_workspace_bytes": (C.c_size_t, [_D]),
     "dynmo_grouped_ffn_bwd": (_I, [_D] + [_P] * 13 + [C.c_size_t, _P]),
+    "dynmo_grouped_ffn_bwd_scatter": (_I, [_D] + [_P] * 16 + [C.c_size_t, _P]),
     "dynmo_combine": (_I, [_D, _P, _P, _P, _P, _P, _P]),
     "dynmo_combine_bwd": (_I, [_D, _P, _P, _P, _P, _P, _P, _P]),
     "dynmo_layer_load": (_I, [_D, _P, C.c_double, C.POINTER(C.c_int32), C.POINTER(C.c_double), _P]),
@@ -234,6 +235,14 @@ def dynmo_grouped_ffn_bwd(d, dy_p, x_p, G_save, U_save, seg_offsets, Wg, Wu, Wd,
     _check("dynmo_grouped_ffn_bwd", lib().dynmo_grouped_ffn_bwd(
         C.byref(d), _ptr(dy_p), _ptr(x_p), _ptr(G_save), _ptr(U_save), _ptr(seg_offsets), _ptr(Wg), _ptr(Wu), _ptr(Wd),
         _ptr(dx_p), _ptr(dWg), _ptr(dWu), _ptr(dWd), _ptr(workspace), workspace.numel(), _stream(stream)))
+
+
+def dynmo_grouped_ffn_bwd_scatter(d, dy_p, x_p, G_save, U_save, seg_offsets, src_slot, Wg, Wu, Wd, dbase, dx, dx_p, dWg,
+                                  dWu, dWd, workspace, stream=None):
+    _check("dynmo_grouped_ffn_bwd_scatter", lib().dynmo_grouped_ffn_bwd_scatter(
+        C.byref(d), _ptr(dy_p), _ptr(x_p), _ptr(G_save), _ptr(U_save), _ptr(seg_offsets), _ptr(src_slot), _ptr(Wg),
+        _ptr(Wu), _ptr(Wd), _ptr(dbase), _ptr(dx), _ptr(dx_p), _ptr(dWg), _ptr(dWu), _ptr(dWd), _ptr(workspace),
+        workspace.numel(), _stream(stream)))
 
 
 def dynmo_combine(d, y_p, dst_pos, gate_w, base, out, stream=None):

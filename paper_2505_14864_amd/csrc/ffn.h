@@ -48,6 +48,8 @@ __device__ __forceinline__ void swiglu_bwd(float dA, float g, float u, float* a,
 
 // The combine of a one-slot layer (k = 1) folded into the stores of Y = A Wd^T: row p also
 // goes to out[t] = res[t] + scale[t] * Y[p], t = scatter[p].  res may be nullptr (zero) or out.
+// The same record folds the scatter back to token order into the stores of dX (backward):
+// scale is then nullptr (weight 1), res the upstream gradient of the residual, out = dx.
 struct FoldedCombine {
   const int32_t* scatter;
   const float* scale;
@@ -57,13 +59,13 @@ struct FoldedCombine {
 
 // In both forward families `gather` is NULL (x_p holds the expert-sorted rows) or the
 // slot index: row p is then x_p[gather[p] / k], x_p being the token-ordered input.
-// `fc` is NULL or the folded combine; y_p may be NULL only with it.
+// `fc` is NULL or the folded combine; y_p (forward) / dx_p (backward) may be NULL only with it.
 int32_t ffn_fwd_generic(const dynmo_desc* d, const void* x_p, const int32_t* gather, const int32_t* seg, const void* Wg,
                         const void* Wu, const void* Wd, void* y_p, void* G, void* U, void* A, const FoldedCombine* fc,
                         hipStream_t st);
 int32_t ffn_bwd_generic(const dynmo_desc* d, const void* dy_p, const void* x_p, const void* G, const void* U,
                         const int32_t* seg, const void* Wg, const void* Wu, const void* Wd, void* dx_p, void* dWg,
-                        void* dWu, void* dWd, void* dG, void* dU, void* A, hipStream_t st);
+                        void* dWu, void* dWd, void* dG, void* dU, void* A, const FoldedCombine* fc, hipStream_t st);
 
 
 // bf16 matrix-core kernels
@@ -74,6 +76,7 @@ int32_t ffn_fwd_mfma(const dynmo_desc* d, const void* x_p, const int32_t* gather
                      const FoldedCombine* fc, hipStream_t st);
 int32_t ffn_bwd_mfma(const dynmo_desc* d, const void* dy_p, const void* x_p, const void* G, const void* U,
                      const int32_t* seg, const void* Wg, const void* Wu, const void* Wd, void* dx_p, void* dWg,
-                     void* dWu, void* dWd, void* dG, void* dU, void* A, void* scratch, hipStream_t st);
+                     void* dWu, void* dWd, void* dG, void* dU, void* A, void* scratch, const FoldedCombine* fc,
+                     hipStream_t st);
 
 }  // namespace dynmo

@@ -78,16 +78,18 @@ extern "C" int32_t dynmo_grouped_ffn_fwd_combine(const dynmo_desc* d, const void
                        workspace, workspace_bytes, &fc, stream);
 }
 
-extern "C" int32_t dynmo_grouped_ffn_bwd(const dynmo_desc* d, const void* dy_p, const void* x_p, const void* G_save,
-                                         const void* U_save, const int32_t* seg_offsets, const void* Wg,
-                                         const void* Wu, const void* Wd, void* dx_p, void* dWg, void* dWu, void* dWd,
-                                         void* workspace, size_t workspace_bytes, void* stream) {
+namespace dynmo {
+static int32_t ffn_bwd_entry(const dynmo_desc* d, const void* dy_p, const void* x_p, const void* G_save,
+                             const void* U_save, const int32_t* seg_offsets, const void* Wg, const void* Wu,
+                             const void* Wd, void* dx_p, void* dWg, void* dWu, void* dWd, void* workspace,
+                             size_t workspace_bytes, const FoldedCombine* fc, void* stream) {
   int32_t rc = check_desc(d);
   if (rc) return rc;
-  if (!dy_p || !x_p || !G_save || !U_save || !seg_offsets || !Wg || !Wu || !Wd || !dx_p || !dWg || !dWu || !dWd ||
-      !workspace)
+  if (!dy_p || !x_p || !G_save || !U_save || !seg_offsets || !Wg || !Wu || !Wd || !dWg || !dWu || !dWd || !workspace)
     return DYNMO_EINVAL;
-  if (misaligned16(dy_p, x_p, G_save, U_save, Wg, Wu, Wd, dx_p, dWg, dWu, dWd)) return DYNMO_EINVAL;
+  if (!dx_p && !fc) return DYNMO_EINVAL;
+  if (misaligned16(dy_p, x_p, G_save, U_save, Wg, Wu, Wd, dx_p, dWg, dWu, dWd) || (fc && misaligned16(fc->res, fc->out)))
+    return DYNMO_EINVAL;
   if (workspace_bytes < dynmo_grouped_ffn_bwd_workspace_bytes(d)) return DYNMO_EWORKSPACE;
   char* base = (char*)align_up((size_t)workspace, 256);
   void* dG = base;
@@ -95,8 +97,30 @@ extern "C" int32_t dynmo_grouped_ffn_bwd(const dynmo_desc* d, const void* dy_p, 
   void* A = base + 2 * act_bytes(d);
   if (ffn_mfma_supported(d))
     return ffn_bwd_mfma(d, dy_p, x_p, G_save, U_save, seg_offsets, Wg, Wu, Wd, dx_p, dWg, dWu, dWd, dG, dU, A,
-                        base + 3 * act_bytes(d), (hipStream_t)stream);
+                        base + 3 * act_bytes(d), fc, (hipStream_t)stream);
   if (max_m_tiles(d, 64) > 65535) return DYNMO_EUNSUPPORTED;  // the generic kernels put row tiles on grid y
-  return ffn_bwd_generic(d, dy_p, x_p, G_save, U_save, seg_offsets, Wg, Wu, Wd, dx_p, dWg, dWu, dWd, dG, dU, A,
+  return ffn_bwd_generic(d, dy_p, x_p, G_save, U_save, seg_offsets, Wg, Wu, Wd, dx_p, dWg, dWu, dWd, dG, dU, A, fc,
                          (hipStream_t)stream);
+}
+}  // namespace dynmo
+
+extern "C" int32_t dynmo_grouped_ffn_bwd(const dynmo_desc* d, const void* dy_p, const void* x_p, const void* G_save,
+                                         const void* U_save, const int32_t* seg_offsets, const void* Wg,
+                                         const void* Wu, const void* Wd, void* dx_p, void* dWg, void* dWu, void* dWd,
+                                         void* workspace, size_t workspace_bytes, void* stream) {
+  return ffn_bwd_entry(d, dy_p, x_p, G_save, U_save, seg_offsets, Wg, Wu, Wd, dx_p, dWg, dWu, dWd, workspace,
+                       workspace_bytes, nullptr, stream);
+}
+
+extern "C" int32_t dynmo_grouped_ffn_bwd_scatter(const dynmo_desc* d, const void* dy_p, const void* x_p,
+                                                 const void* G_save, const void* U_save, const int32_t* seg_offsets,
+                                                 const int32_t* src_slot, const void* Wg, const void* Wu,
+                                                 const void* Wd, const void* dbase, void* dx, void* dx_p, void* dWg,
+                                                 void* dWu, void* dWd, void* workspace, size_t workspace_bytes,
+                                                 void* stream) {
+  if (!d || !src_slot || !dx) return DYNMO_EINVAL;
+  if (d->k != 1) return DYNMO_EINVAL;  // with two slots per token two rows would meet in one row of dx
+  const FoldedCombine fc = {src_slot, nullptr, dbase, dx};
+  return ffn_bwd_entry(d, dy_p, x_p, G_save, U_save, seg_offsets, Wg, Wu, Wd, dx_p, dWg, dWu, dWd, workspace,
+                       workspace_bytes, &fc, stream);
 }

@@ -140,7 +140,7 @@ __global__ __launch_bounds__(256) void seg_gemm_generic_kernel(const int32_t* __
         if (scatter) {  // folded combine of a one-slot layer
           const int token = scatter[m];
           const long ot = (long)token * N + n;
-          Elem<T>::store(out + ot, (res ? Elem<T>::load(res + ot) : 0.f) + scale[token] * acc[i][j]);
+          Elem<T>::store(out + ot, (res ? Elem<T>::load(res + ot) : 0.f) + (scale ? scale[token] : 1.f) * acc[i][j]);
         }
       } else {
         const float g = Elem<T>::load(Gs + o), u = Elem<T>::load(Us + o);
@@ -199,7 +199,7 @@ static int32_t fwd_generic_t(const dynmo_desc* d, const void* x_p, const int32_t
 template <typename T>
 static int32_t bwd_generic_t(const dynmo_desc* d, const void* dy_p, const void* x_p, const void* G, const void* U,
                              const int32_t* seg, const void* Wg, const void* Wu, const void* Wd, void* dx_p, void* dWg,
-                             void* dWu, void* dWd, void* dG, void* dU, void* A, hipStream_t st) {
+                             void* dWu, void* dWd, void* dG, void* dU, void* A, const FoldedCombine* fc, hipStream_t st) {
   const int m_tiles = max_m_tiles(d, GT);
   const long FH = (long)d->F * d->H;
   const unsigned tf = (d->F + GT - 1) / GT, th = (d->H + GT - 1) / GT;
@@ -211,7 +211,8 @@ static int32_t bwd_generic_t(const dynmo_desc* d, const void* dy_p, const void* 
     // dX = dG Wg + dU Wu : B(n=h, k=f) = W[e][f*H + h]
     DYNMO_TIMED_LAUNCH(K_FFN_DX, st, seg_gemm_generic_kernel<T, EPI_STORE><<<dim3(th, m_tiles), dim3(256), 0, st>>>(
         seg, d->E, d->H, d->F, (const T*)dG, (const T*)Wg, (const T*)dU, (const T*)Wu, d->F, FH, 1, d->H, (T*)dx_p, nullptr,
-        nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr));
+        nullptr, nullptr, nullptr, nullptr, fc ? fc->scatter : nullptr, fc ? fc->scale : nullptr,
+        fc ? (const T*)fc->res : nullptr, fc ? (T*)fc->out : nullptr));
   }
   // The weight gradients are written for every expert, rows or not.
   DYNMO_TIMED_LAUNCH(K_FFN_DWD, st,
@@ -235,10 +236,10 @@ int32_t ffn_fwd_generic(const dynmo_desc* d, const void* x_p, const int32_t* gat
 
 int32_t ffn_bwd_generic(const dynmo_desc* d, const void* dy_p, const void* x_p, const void* G, const void* U,
                         const int32_t* seg, const void* Wg, const void* Wu, const void* Wd, void* dx_p, void* dWg,
-                        void* dWu, void* dWd, void* dG, void* dU, void* A, hipStream_t st) {
+                        void* dWu, void* dWd, void* dG, void* dU, void* A, const FoldedCombine* fc, hipStream_t st) {
   return d->dtype == DYNMO_BF16
-             ? bwd_generic_t<bf16_t>(d, dy_p, x_p, G, U, seg, Wg, Wu, Wd, dx_p, dWg, dWu, dWd, dG, dU, A, st)
-             : bwd_generic_t<float>(d, dy_p, x_p, G, U, seg, Wg, Wu, Wd, dx_p, dWg, dWu, dWd, dG, dU, A, st);
+             ? bwd_generic_t<bf16_t>(d, dy_p, x_p, G, U, seg, Wg, Wu, Wd, dx_p, dWg, dWu, dWd, dG, dU, A, fc, st)
+             : bwd_generic_t<float>(d, dy_p, x_p, G, U, seg, Wg, Wu, Wd, dx_p, dWg, dWu, dWd, dG, dU, A, fc, st);
 }
 
 }  // namespace dynmo

@@ -66,8 +66,9 @@ constexpr int kSplitHdrInts = 4 + 4 * kMaxSplitTiles;  // {split, patches, slots
 static_assert(2 * kStageBytes <= kLdsBytes, "the two stages must fit in front of the tile table");
 static_assert(kPieces * kWaves == 32, "a tile is 32 pieces of 1 KB");
 
-// MODE_DOWN_FOLD is MODE_DOWN with the weighted combine of a one-slot layer in its stores
-enum { MODE_GATEUP = 0, MODE_DOWN = 1, MODE_DA = 2, MODE_DX = 3, MODE_DW = 4, MODE_DOWN_FOLD = 5 };
+// MODE_DOWN_FOLD is MODE_DOWN with the weighted combine of a one-slot layer in its stores;
+// MODE_DX_FOLD is MODE_DX with the scatter back to token order (weight 1) in its stores
+enum { MODE_GATEUP = 0, MODE_DOWN = 1, MODE_DA = 2, MODE_DX = 3, MODE_DW = 4, MODE_DOWN_FOLD = 5, MODE_DX_FOLD = 6 };
 
 struct GemmParams {
   const int32_t* seg;
@@ -91,8 +92,8 @@ struct GemmParams {
   float* partial;     // kMaxPersistent fp32 partial tiles, then kSplitHdrInts ints (modes that may split k)
   const int32_t* gather;  // MODE_GATEUP: row p of operand A is row gather[p] / gather_div of A1, or nullptr
   int gather_div;
-  // MODE_DOWN_FOLD (k = 1): row p also goes to row t = scatter[p] of out as
-  // res[t] + scale[t] * value (res nullptr = 0; res may be out); C0 may then be nullptr
+  // MODE_DOWN_FOLD / MODE_DX_FOLD (k = 1): row p also goes to row t = scatter[p] of out as
+  // res[t] + scale[t] * value (res nullptr = 0; res may be out; scale nullptr = 1); C0 may then be nullptr
   const int32_t* scatter;
   const float* scale;
   const bf16_t* res;
@@ -384,7 +385,9 @@ template <int MODE>
 __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmParams p) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr bool A_TRANS = MODE == MODE_DW;
-  constexpr bool B_TRANS = MODE == MODE_DA || MODE == MODE_DX || MODE == MODE_DW;
+  constexpr bool IS_DX = MODE == MODE_DX || MODE == MODE_DX_FOLD;
+  constexpr bool FOLDS = MODE == MODE_DOWN_FOLD || MODE == MODE_DX_FOLD;
+  constexpr bool B_TRANS = MODE == MODE_DA || IS_DX || MODE == MODE_DW;
   constexpr int TILE_N = MODE == MODE_GATEUP ? 128 : BN;  // output columns per tile
 
   // Persistent workgroups: workgroup b belongs to XCD b % 8 (the hardware deals
@@ -408,7 +411,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   // at once, every one on its own chunk of the k range: a patch keeps the operand
   // sharing of an ordinary round.  The chunks leave fp32 partial tiles in global memory,
   // which a second small kernel adds up in chunk order and converts.
-  constexpr bool CAN_SPLIT = MODE == MODE_DOWN || MODE == MODE_DOWN_FOLD || MODE == MODE_DX;
+  constexpr bool CAN_SPLIT = MODE == MODE_DOWN || MODE == MODE_DOWN_FOLD || IS_DX;
   const int slot = blockIdx.x / kXcds;
   int first = 0, mine = tb.total;  // this XCD's run of the list
   int split = 1, patches = 0, tail_tiles = 0;
@@ -417,7 +420,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     if (CAN_SPLIT && p.partial != nullptr) {
       tail_tiles = all % (int)gridDim.x;
       patches = (tail_tiles + slots - 1) / slots;
-      const int kts = (p.K + BK - 1) / BK * (MODE == MODE_DX ? 2 : 1);
+      const int kts = (p.K + BK - 1) / BK * (IS_DX ? 2 : 1);
       if (tail_tiles > 0 && 2 * patches <= kXcds) split = max(1, min(kXcds / patches, kts / kMinSplitKt));
       if (split == 1) tail_tiles = 0;
     }
@@ -444,8 +447,8 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   // contraction range and per-expert operand bases
   const int k_begin = MODE == MODE_DW ? t.k_begin : 0, k_end = MODE == MODE_DW ? t.k_end : p.K;
   const bf16_t* B1 = p.B1 + (MODE == MODE_DW ? 0 : (long)t.e * p.b_expert_stride);
-  const bf16_t* B2 = (MODE == MODE_GATEUP || MODE == MODE_DX) ? p.B2 + (long)t.e * p.b_expert_stride : nullptr;
-  const int phases = MODE == MODE_DX ? 2 : 1;
+  const bf16_t* B2 = (MODE == MODE_GATEUP || IS_DX) ? p.B2 + (long)t.e * p.b_expert_stride : nullptr;
+  const int phases = IS_DX ? 2 : 1;
   const int kt_per_phase = (k_end - k_begin + BK - 1) / BK;
   const int n_kt = kt_per_phase * phases;
   const int kt_lo = parted ? chunk * n_kt / split : 0, kt_hi = parted ? (chunk + 1) * n_kt / split : n_kt;
@@ -501,13 +504,13 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     int k_left;
   };
   auto ktile = [&](int kt) {
-    int ph = MODE == MODE_DX ? kt / kt_per_phase : 0;
-    if (MODE == MODE_DX && ph > 1) ph = 1;
+    int ph = IS_DX ? kt / kt_per_phase : 0;
+    if (IS_DX && ph > 1) ph = 1;
     const int k0 = k_begin + (kt - ph * kt_per_phase) * BK;
     KTile q;
     q.k_left = kt < kt_hi ? k_end - k0 : 0;
     const bf16_t* A = ph == 0 ? p.A1 : p.A2;
-    const bf16_t* B = ((MODE == MODE_DX && ph == 1) || second_b) ? B2 : B1;
+    const bf16_t* B = ((IS_DX && ph == 1) || second_b) ? B2 : B1;
     q.a = make_desc(A_TRANS ? A + (long)k0 * p.lda + t.m0 : A + (gathered ? 0 : (long)t.m0 * p.lda) + k0, 0x7ffffffeu);
     q.b = make_desc(B_TRANS ? B + (long)k0 * p.ldb + t.n0 : B + (long)t.n0 * p.ldb + k0, 0x7ffffffeu);
     return q;
@@ -645,7 +648,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     int token[8];
     float weight[8];
     u32x4 resid[8];
-    const bool fold = MODE == MODE_DOWN_FOLD && !parted;
+    const bool fold = FOLDS && !parted;
     if (fold) {
 #pragma unroll
       for (int s = 0; s < 8; ++s) {
@@ -662,7 +665,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
       const int col = t.n0 + wn * 128 + (lane & 15) * 8;
 #pragma unroll
       for (int s = 0; s < 8; ++s) {
-        weight[s] = p.scale[token[s]];
+        weight[s] = p.scale ? p.scale[token[s]] : 1.f;
         resid[s] = u32x4{0u, 0u, 0u, 0u};
         if (p.res && col < n_end) resid[s] = *(const u32x4*)(p.res + (long)token[s] * p.ldc + col);
       }
@@ -713,8 +716,8 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
             *(u32x4*)(C2 + o) = pack16<bf16_t>(a_);
           }
         } else if (ok) {
-          if (MODE != MODE_DOWN_FOLD || C0) *(u32x4*)(C0 + o) = pack16<bf16_t>(v);
-          if (MODE == MODE_DOWN_FOLD) {
+          if (!FOLDS || C0) *(u32x4*)(C0 + o) = pack16<bf16_t>(v);
+          if (FOLDS) {
             float r[8];
             unpack16<bf16_t>(resid[s], r);
 #pragma unroll
@@ -764,7 +767,7 @@ __global__ __launch_bounds__(256) void ffn_split_reduce_kernel(const float* __re
       token[it] = scatter[row < m_end ? row : m0];
     }
 #pragma unroll
-    for (int it = 0; it < kReduceIters; ++it) weight[it] = scale[token[it]];
+    for (int it = 0; it < kReduceIters; ++it) weight[it] = scale ? scale[token[it]] : 1.f;
   }
 #pragma unroll
   for (int it = 0; it < kReduceIters; ++it) {
@@ -840,7 +843,7 @@ static int32_t launch_mfma(const GemmParams& p, int max_tiles, KernelId id, hipS
   }
   if (max_tiles <= 0) return DYNMO_OK;
   // a product that may split k always brings every compute unit: few tiles is when it splits
-  const bool may_split = (MODE == MODE_DOWN || MODE == MODE_DOWN_FOLD || MODE == MODE_DX) && p.partial != nullptr;
+  const bool may_split = (MODE == MODE_DOWN || MODE == MODE_DOWN_FOLD || MODE == MODE_DX || MODE == MODE_DX_FOLD) && p.partial != nullptr;
   const int blocks = persistent_blocks(may_split ? kMaxPersistent : max_tiles);
   ProfScope prof(id, st);
   ffn_mfma_kernel<MODE><<<dim3(blocks), dim3(kMfmaThreads), kLdsBytes + kTableBytes, st>>>(p);
@@ -909,7 +912,8 @@ int32_t ffn_fwd_mfma(const dynmo_desc* d, const void* x_p, const int32_t* gather
 
 int32_t ffn_bwd_mfma(const dynmo_desc* d, const void* dy_p, const void* x_p, const void* G, const void* U,
                      const int32_t* seg, const void* Wg, const void* Wu, const void* Wd, void* dx_p, void* dWg,
-                     void* dWu, void* dWd, void* dG, void* dU, void* A, void* scratch, hipStream_t st) {
+                     void* dWu, void* dWd, void* dG, void* dU, void* A, void* scratch, const FoldedCombine* fc,
+                     hipStream_t st) {
   const int mt = max_m_tiles(d, BM);
   const long FH = (long)d->F * d->H;
   const int tH = (d->H + BN - 1) / BN, tF = (d->F + BN - 1) / BN;
@@ -969,6 +973,13 @@ int32_t ffn_bwd_mfma(const dynmo_desc* d, const void* dy_p, const void* x_p, con
     p.b_expert_stride = FH;
     p.C0 = (bf16_t*)dx_p;
     p.ldc = d->H;
+    if (fc) {
+      p.scatter = fc->scatter;
+      p.scale = fc->scale;
+      p.res = (const bf16_t*)fc->res;
+      p.out = (bf16_t*)fc->out;
+      return launch_mfma<MODE_DX_FOLD>(p, mt * tH, K_FFN_DX, st);
+    }
     return launch_mfma<MODE_DX>(p, mt * tH, K_FFN_DX, st);
   }
 }

@@ -136,6 +136,22 @@ class RoutedFFNLayer:
         B.dynmo_permute_bwd(d, self.dx_p, self.dst_pos, dout if self.residual else None, dx)
         return dx
 
+    def backward_folded(self, dout, Wg, Wu, Wd, dx=None):
+        """k = 1 only: the scatter back to token order folded into the stores of the dX product.
+        A layer with a residual ("mod", "early_exit") updates dout in place and returns it (the
+        gradient of a token without a routed row passes through untouched); with `dx` given it
+        writes the routed tokens' rows of `dx` instead (dbase = dout) and the other rows of
+        `dx` are the caller's.  A top-1 "moe" layer writes self.dx (every token has a row)."""
+        self.alloc_backward()
+        d = self.d
+        if dx is None:
+            dx = dout if self.residual else self.dx
+        B.dynmo_combine_bwd(d, dout, self.y_p, self.dst_pos, self.gate_w, self.dy_p, self.dgate)
+        B.dynmo_grouped_ffn_bwd_scatter(d, self.dy_p, self.x_p, self.G, self.U, self.seg_offsets, self.src_slot, Wg, Wu,
+                                        Wd, dout if self.residual else None, dx, None, self.dWg, self.dWu, self.dWd,
+                                        self.ws_bwd)
+        return dx
+
     def route_bwd(self, scores=None):
         self.alloc_backward()
         if self.mode == "moe":

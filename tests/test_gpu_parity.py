@@ -862,6 +862,63 @@ def test_forward_with_folded_combine(mode, w):
     assert torch.equal(G[:R], b.G[:R]) and torch.equal(U[:R], b.U[:R])
 
 
+@pytest.mark.parametrize("mode,w", FOLDED_CASES,
+                         ids=lambda v: v if isinstance(v, str) else "%s-T%d-H%d-F%d" % (v.dtype, v.T, v.H, v.F))
+def test_backward_with_folded_scatter(mode, w):
+    """k = 1: the dX product stores dbase + dX straight into the token rows (the scatter back to
+    token order folded into its stores).  Checked against the oracle's dx; the gradient rows of
+    tokens without a routed row keep their bits; the weight gradients and the gate gradient are
+    those of the plain backward pass bit for bit."""
+    say("folded scatter %s %s T=%d H=%d F=%d" % (mode, w.dtype, w.T, w.H, w.F))
+    inp = wl.make_inputs(w, threads=1)
+    dev = {n: to_device(a) for n, a in inp.items()}
+    a = RoutedFFNLayer(w.T, w.H, w.F, w.E, w.k, w.dtype, mode)
+    b = RoutedFFNLayer(w.T, w.H, w.F, w.E, w.k, w.dtype, mode)
+    for layer in (a, b):
+        route_for(layer, mode, w, dev)
+        layer.forward(dev["x"], dev["Wg"], dev["Wu"], dev["Wd"])
+    dx_a = a.backward(dev["dout"], dev["Wg"], dev["Wu"], dev["Wd"])
+    g_b = dev["dout"].clone()
+    dx_b = b.backward_folded(g_b, dev["Wg"], dev["Wu"], dev["Wd"])
+    assert (dx_b is g_b) == (mode != "moe")
+    torch.cuda.synchronize()
+    f = f32_inputs(inp)
+    if mode == "moe":
+        ref = orc.moe_layer(f["logits"], f["x"], f["Wg"], f["Wu"], f["Wd"], w.k, f["dout"])
+    else:
+        ref = orc.mod_layer(f["scores"], w.cap, f["x"], f["Wg"], f["Wu"], f["Wd"], f["dout"])
+    e_dx = assert_close("dx", to_host(dx_b), ref["dx"], TOL[w.dtype])
+    unrouted = torch.as_tensor(ref["expert_idx"][:, 0] < 0, device="cuda")
+    if mode != "moe":
+        assert torch.equal(dx_b[unrouted], dev["dout"][unrouted])
+    else:
+        assert not bool(unrouted.any())
+    # one rounding instead of two: never further from the plain result than two output steps
+    step = 2.0 ** -7 if w.dtype == "bf16" else 2.0 ** -22
+    assert_close("dx vs plain", to_host(dx_b), to_host(dx_a), 2 * step)
+    for n in ("dWg", "dWu", "dWd", "dgate"):
+        assert torch.equal(getattr(a, n), getattr(b, n)), n
+    R = int(to_host(a.seg_offsets)[-1])
+    assert torch.equal(a.dy_p[:R], b.dy_p[:R])
+    say("  dx err %.1e" % e_dx)
+
+    # a separate dx with dbase given, and the rows in expert order asked for as well
+    dx_c = torch.full_like(dev["dout"], 3.0)
+    dx_p = torch.empty_like(b.dx_p)
+    B.dynmo_grouped_ffn_bwd_scatter(b.d, b.dy_p, b.x_p, b.G, b.U, b.seg_offsets, b.src_slot, dev["Wg"], dev["Wu"],
+                                    dev["Wd"], dev["dout"] if mode != "moe" else None, dx_c, dx_p, b.dWg, b.dWu, b.dWd,
+                                    b.ws_bwd)
+    torch.cuda.synchronize()
+    routed = ~unrouted
+    assert torch.equal(dx_c[routed], dx_b[routed])
+    assert bool((dx_c[unrouted] == 3.0).all())
+    assert torch.equal(dx_p[:R], a.dx_p[:R])
+    d2 = B.make_desc(w.T, w.H, w.F, max(2, w.E), 2, w.dtype)
+    with pytest.raises(B.DynmoError):
+        B.dynmo_grouped_ffn_bwd_scatter(d2, b.dy_p, b.x_p, b.G, b.U, b.seg_offsets, b.src_slot, dev["Wg"], dev["Wu"],
+                                        dev["Wd"], None, dx_c, None, b.dWg, b.dWu, b.dWd, b.ws_bwd)
+
+
 def test_folded_combine_early_exit_stack_in_place():
     """Sec. 2.5's shrinking stack with the residual stream updated in place, layer after layer."""
     say("folded combine, early-exit stack in place")
@@ -873,9 +930,9 @@ def test_folded_combine_early_exit_stack_in_place():
     for l, layer in enumerate(layers):
         layer.route_active(dev["exit_layer"], l + 1)
         assert layer.forward_folded(x, dev["Wg"][l], dev["Wu"][l], dev["Wd"][l]) is x
-    g = dev["dout"]
+    g = dev["dout"].clone()
     for l in range(w.layers - 1, -1, -1):
-        g = layers[l].backward(g, dev["Wg"][l], dev["Wu"][l], dev["Wd"][l])
+        assert layers[l].backward_folded(g, dev["Wg"][l], dev["Wu"][l], dev["Wd"][l]) is g
     torch.cuda.synchronize()
     plain_layers, plain_out, plain_dx = run_stack(w, inp)
     f = f32_inputs(inp)
@@ -885,6 +942,7 @@ def test_folded_combine_early_exit_stack_in_place():
     assert_close("dx", to_host(g), ref["dx"], TOL["bf16"])
     # the in-place stream rounds once per layer where the plain one rounds twice
     assert_close("out vs plain", to_host(x), to_host(plain_out), 4 * 2.0 ** -7)
+    assert_close("dx vs plain", to_host(g), to_host(plain_dx), 4 * 2.0 ** -7)
     assert [l.load()[0] for l in layers] == [l.load()[0] for l in plain_layers]
 
 
