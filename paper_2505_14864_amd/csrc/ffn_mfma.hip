@@ -52,8 +52,12 @@ constexpr int kPieces = 32 / kWaves;           // 1 KB pieces of an operand tile
 constexpr int kTileBytes = 256 * 64 * 2;       // one operand tile (256 rows x 64 k, bf16), unpadded
 constexpr int kStageBytes = 2 * kTileBytes;    // A then B
 constexpr int kEpPitch = 136;                  // floats per row of an epilogue LDS patch (128 + 8 pad)
-constexpr int kEpWaveBytes = 32 * kEpPitch * 4;  // one 32-row band per wavefront
-constexpr int kLdsBytes = kWaves * kEpWaveBytes;  // the epilogue patches; the two stages fit inside
+constexpr int kEpRows = 16;                    // rows a wavefront passes through its patch at a time
+constexpr int kEpWaveBytes = kEpRows * kEpPitch * 4;
+// The epilogue patches lie behind stage 0, which is free while they are in use: the next
+// tile's first k tile is loaded into it meanwhile.
+constexpr int kEpBase = kStageBytes;
+constexpr int kLdsBytes = kEpBase + kWaves * kEpWaveBytes;  // >= the two stages
 constexpr int kTableBytes = 64 * 8 * 4;        // the per-expert tile table, kept behind them
 constexpr int kXcds = 8;
 constexpr int kGroupN = 8;                   // column tiles that run side by side in one XCD
@@ -64,6 +68,7 @@ constexpr size_t kPartialFloats = (size_t)BM * BN;     // one workgroup's fp32 p
 constexpr int kSplitHdrInts = 4 + 4 * kMaxSplitTiles;  // {split, patches, slots, tiles} + {m0, m_end, n0, -} per tile
 
 static_assert(2 * kStageBytes <= kLdsBytes, "the two stages must fit in front of the tile table");
+static_assert(kLdsBytes + kTableBytes <= 160 * 1024, "LDS of one compute unit");
 static_assert(kPieces * kWaves == 32, "a tile is 32 pieces of 1 KB");
 
 // MODE_DOWN_FOLD is MODE_DOWN with the weighted combine of a one-slot layer in its stores;
@@ -438,20 +443,73 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     hdr[2] = slots;
     hdr[3] = tail_tiles;
   }
-  for (int round = 0; round < my_rounds + (has_part ? 1 : 0); ++round) {
+  const int wave_u = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  // the gate/up pairing: LDS rows 128..255 of operand B (the upper four wavefronts' pieces) come from the second matrix
+  const bool second_b = MODE == MODE_GATEUP && wave_u >= kWaves / 2;
+  const bool gathered = MODE == MODE_GATEUP && p.gather != nullptr;
+  const uint32_t lda_b = (uint32_t)p.lda * 2, ldb_b = (uint32_t)p.ldb * 2;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)smem;  // LDS addresses are 32-bit offsets
+  auto pieces_a = [&](const Tile& tt) {
+    return A_TRANS   ? pieces_krow(lda_b, tt.m_end - tt.m0)
+           : gathered ? pieces_rowk_gather(lda_b, tt.m0, tt.m_end - tt.m0, p.gather, p.gather_div)
+                      : pieces_rowk(lda_b, tt.m_end - tt.m0, 256);
+  };
+  auto pieces_b = [&](const Tile& tt) {
+    return B_TRANS ? pieces_krow(ldb_b, n_end - tt.n0) : pieces_rowk(ldb_b, n_end - tt.n0, MODE == MODE_GATEUP ? 128 : 256);
+  };
+  // operand descriptors of one k tile (wave-uniform), and how many k are left in it
+  struct KTile {
+    desc_t a, b;
+    int k_left;
+  };
+  // The k range a workgroup covers of tile tt: all of it, or its chunk of a split tile.
+  struct KRange {
+    int k_begin, k_end, kt_per_phase, kt_lo, kt_hi;
+  };
+  auto krange = [&](const Tile& tt, bool parted_t) {
+    KRange r;
+    r.k_begin = MODE == MODE_DW ? tt.k_begin : 0;
+    r.k_end = MODE == MODE_DW ? tt.k_end : p.K;
+    r.kt_per_phase = (r.k_end - r.k_begin + BK - 1) / BK;
+    const int n_kt = r.kt_per_phase * (IS_DX ? 2 : 1);
+    const int chunk_t = parted_t ? xcd % split : 0;
+    r.kt_lo = parted_t ? chunk_t * n_kt / split : 0;
+    r.kt_hi = parted_t ? (chunk_t + 1) * n_kt / split : n_kt;
+    return r;
+  };
+  auto ktile_of = [&](const Tile& tt, const KRange& r, int kt) {
+    int ph = IS_DX ? kt / r.kt_per_phase : 0;
+    if (IS_DX && ph > 1) ph = 1;
+    const int k0 = r.k_begin + (kt - ph * r.kt_per_phase) * BK;
+    KTile q;
+    q.k_left = kt < r.kt_hi ? r.k_end - k0 : 0;
+    const bf16_t* A = ph == 0 ? p.A1 : p.A2;
+    const bf16_t* Bw = ((IS_DX && ph == 1) || second_b) ? p.B2 : p.B1;
+    const bf16_t* B = Bw + (MODE == MODE_DW ? 0 : (long)tt.e * p.b_expert_stride);
+    q.a = make_desc(A_TRANS ? A + (long)k0 * p.lda + tt.m0 : A + (gathered ? 0 : (long)tt.m0 * p.lda) + k0, 0x7ffffffeu);
+    q.b = make_desc(B_TRANS ? B + (long)k0 * p.ldb + tt.n0 : B + (long)tt.n0 * p.ldb + k0, 0x7ffffffeu);
+    return q;
+  };
+  // this wavefront's pieces of k tile q (pieces pa / pb) into the stage at LDS offset `stage`
+  auto dma_a = [&](const Pieces& pa, const KTile& q, uint32_t stage, int j) {
+    load_to_lds(q.a, stage + (wave_u * kPieces + j) * 1024, pa.kpos[j] < q.k_left ? pa.off[j] : kOob);
+  };
+  auto dma_b = [&](const Pieces& pb, const KTile& q, uint32_t stage, int j) {
+    load_to_lds(q.b, stage + kTileBytes + (wave_u * kPieces + j) * 1024, pb.kpos[j] < q.k_left ? pb.off[j] : kOob);
+  };
+  const int n_rounds = my_rounds + (has_part ? 1 : 0);
+  auto tile_at = [&](int round) {
+    const bool parted_t = CAN_SPLIT && round == my_rounds;
+    return decode_tile(table, tb, parted_t ? tb.total - tail_tiles + tail_tile : first + round * slots + slot,
+                       MODE == MODE_DW, p.M, TILE_N);
+  };
+  bool first_in_flight = false;  // the first k tile of the tile about to start is already on its way to stage 0
+  for (int round = 0; round < n_rounds; ++round) {
   const bool parted = CAN_SPLIT && round == my_rounds;
   const int chunk = parted ? xcd % split : 0;
-  const Tile t = decode_tile(table, tb, parted ? tb.total - tail_tiles + tail_tile : first + round * slots + slot,
-                             MODE == MODE_DW, p.M, TILE_N);
-
-  // contraction range and per-expert operand bases
-  const int k_begin = MODE == MODE_DW ? t.k_begin : 0, k_end = MODE == MODE_DW ? t.k_end : p.K;
-  const bf16_t* B1 = p.B1 + (MODE == MODE_DW ? 0 : (long)t.e * p.b_expert_stride);
-  const bf16_t* B2 = (MODE == MODE_GATEUP || IS_DX) ? p.B2 + (long)t.e * p.b_expert_stride : nullptr;
-  const int phases = IS_DX ? 2 : 1;
-  const int kt_per_phase = (k_end - k_begin + BK - 1) / BK;
-  const int n_kt = kt_per_phase * phases;
-  const int kt_lo = parted ? chunk * n_kt / split : 0, kt_hi = parted ? (chunk + 1) * n_kt / split : n_kt;
+  const Tile t = tile_at(round);
+  const KRange kr = krange(t, parted);
+  const int kt_lo = kr.kt_lo, kt_hi = kr.kt_hi;
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm = wave >> 1, wn = wave & 1;  // 4 x 2 wavefronts, 64 x 128 outputs each
@@ -481,47 +539,13 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   // of them would hold up the wavefront's own MFMAs.  Past the last tile the loads are
   // masked (zeros, no memory access), which keeps the loop body free of branches.
   bf16x8_t fa[2][2], fb[2][4];
-  const uint32_t lda_b = (uint32_t)p.lda * 2, ldb_b = (uint32_t)p.ldb * 2;
-  const bool gathered = MODE == MODE_GATEUP && p.gather != nullptr;
-  const Pieces pa = A_TRANS   ? pieces_krow(lda_b, t.m_end - t.m0)
-                    : gathered ? pieces_rowk_gather(lda_b, t.m0, t.m_end - t.m0, p.gather, p.gather_div)
-                               : pieces_rowk(lda_b, t.m_end - t.m0, 256);
-  const Pieces pb = B_TRANS ? pieces_krow(ldb_b, n_end - t.n0)
-                            : pieces_rowk(ldb_b, n_end - t.n0, MODE == MODE_GATEUP ? 128 : 256);
-  const int wave_u = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  // the gate/up pairing: LDS rows 128..255 of operand B (the upper four wavefronts' pieces) come from the second matrix
-  const bool second_b = MODE == MODE_GATEUP && wave_u >= kWaves / 2;
+  const Pieces pa = pieces_a(t), pb = pieces_b(t);
   // the 32-row blocks this wavefront reads: two of A, four of B (gate/up: two gate blocks and the two matching up blocks)
   constexpr int kBlocksA[4] = {0, 1, 0, 0};
   constexpr int kBlocksB[4] = {0, 1, MODE == MODE_GATEUP ? 4 : 2, MODE == MODE_GATEUP ? 5 : 3};
   const FragAddr fra = frag_addr<A_TRANS>((wave_u >> 1) * 2, kBlocksA);
   const FragAddr frb = frag_addr<B_TRANS>(MODE == MODE_GATEUP ? (wave_u & 1) * 2 : (wave_u & 1) * 4, kBlocksB);
-  const uint32_t lds0 = (uint32_t)(uintptr_t)smem;  // LDS addresses are 32-bit offsets
-
-  // operand descriptors of k tile kt (wave-uniform), and how many k are left in it
-  struct KTile {
-    desc_t a, b;
-    int k_left;
-  };
-  auto ktile = [&](int kt) {
-    int ph = IS_DX ? kt / kt_per_phase : 0;
-    if (IS_DX && ph > 1) ph = 1;
-    const int k0 = k_begin + (kt - ph * kt_per_phase) * BK;
-    KTile q;
-    q.k_left = kt < kt_hi ? k_end - k0 : 0;
-    const bf16_t* A = ph == 0 ? p.A1 : p.A2;
-    const bf16_t* B = ((IS_DX && ph == 1) || second_b) ? B2 : B1;
-    q.a = make_desc(A_TRANS ? A + (long)k0 * p.lda + t.m0 : A + (gathered ? 0 : (long)t.m0 * p.lda) + k0, 0x7ffffffeu);
-    q.b = make_desc(B_TRANS ? B + (long)k0 * p.ldb + t.n0 : B + (long)t.n0 * p.ldb + k0, 0x7ffffffeu);
-    return q;
-  };
-  // piece j of this wavefront, operand A / B of k tile q, into the stage at LDS offset `stage`
-  auto dma_a = [&](const KTile& q, uint32_t stage, int j) {
-    load_to_lds(q.a, stage + (wave_u * kPieces + j) * 1024, pa.kpos[j] < q.k_left ? pa.off[j] : kOob);
-  };
-  auto dma_b = [&](const KTile& q, uint32_t stage, int j) {
-    load_to_lds(q.b, stage + kTileBytes + (wave_u * kPieces + j) * 1024, pb.kpos[j] < q.k_left ? pb.off[j] : kOob);
-  };
+  auto ktile = [&](int kt) { return ktile_of(t, kr, kt); };
   // fragment f of k step KS: 0..1 = row blocks of A, 2..5 = column blocks of B
   auto read_frag = [&](auto BUF, auto F, const char* stage, auto KS) {
     constexpr int Q = decltype(BUF)::value, f = decltype(F)::value, ks = decltype(KS)::value;
@@ -541,13 +565,15 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   const std::integral_constant<int, 2> c2;
   const std::integral_constant<int, 3> c3;
 
-  {
+  if (!first_in_flight) {
     const KTile q0 = ktile(kt_lo);
-    static_for<kPieces>([&](auto J) { dma_a(q0, lds0, J); });
-    static_for<kPieces>([&](auto J) { dma_b(q0, lds0, J); });
+    static_for<kPieces>([&](auto J) { dma_a(pa, q0, lds0, J); });
+    static_for<kPieces>([&](auto J) { dma_b(pb, q0, lds0, J); });
+  }
+  {
     const KTile q1 = ktile(kt_lo + 1);
-    static_for<kPieces>([&](auto J) { dma_a(q1, lds0 + kStageBytes, J); });
-    static_for<kPieces>([&](auto J) { dma_b(q1, lds0 + kStageBytes, J); });
+    static_for<kPieces>([&](auto J) { dma_a(pa, q1, lds0 + kStageBytes, J); });
+    static_for<kPieces>([&](auto J) { dma_b(pb, q1, lds0 + kStageBytes, J); });
   }
   wait_loads_but<2 * kPieces>();  // the first tile has landed
   wg_barrier();
@@ -563,8 +589,8 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
       wg_barrier();
       const uint32_t freed = lds0 + ((kt - kt_lo) & 1) * kStageBytes;
       const KTile q2 = ktile(kt + 2);
-      static_for<kPieces>([&](auto J) { dma_a(q2, freed, J); });
-      static_for<kPieces>([&](auto J) { dma_b(q2, freed, J); });
+      static_for<kPieces>([&](auto J) { dma_a(pa, q2, freed, J); });
+      static_for<kPieces>([&](auto J) { dma_b(pb, q2, freed, J); });
     }
   } else {
   static_for<6>([&](auto F) { read_frag(c0, F, smem, c0); });
@@ -600,21 +626,35 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     // step 3: the next tile's first fragments, and the refill of the stage just freed
     static_for<8>([&](auto M) {
       if constexpr (M < 6) read_frag(c0, M, next, c0);
-      if constexpr (M < kPieces) dma_a(q2, freed, M);
-      else dma_b(q2, freed, M - kPieces);
+      if constexpr (M < kPieces) dma_a(pa, q2, freed, M);
+      else dma_b(pb, q2, freed, M - kPieces);
       mfma(c1, M);
       __builtin_amdgcn_sched_barrier(0);
     });
   }
   }  // has_work
-  // the stages become the epilogue's patches: every piece (masked ones included) has landed
+  // every piece (masked ones included) has landed and nobody reads the stages any more
   wait_loads_and_lds();
   wg_barrier();
+  // The epilogue uses patches behind stage 0, so the first k tile of this workgroup's next
+  // tile can be on its way into stage 0 while the results are stored.
+  first_in_flight = round + 1 < n_rounds;
+  if (first_in_flight) {
+    const Tile tn = tile_at(round + 1);
+    const KRange rn = krange(tn, CAN_SPLIT && round + 1 == my_rounds);
+    const Pieces pan = pieces_a(tn), pbn = pieces_b(tn);
+    const KTile qn = ktile_of(tn, rn, rn.kt_lo);
+    static_for<kPieces>([&](auto J) { dma_a(pan, qn, lds0, J); });
+    static_for<kPieces>([&](auto J) { dma_b(pbn, qn, lds0, J); });
+  }
 
   // ---- epilogue.  Accumulator element r of block (i, j) is row i*32 + (r/4)*8 +
   // (lane/32)*4 + r%4, column j*32 + lane%32 of the wavefront's 64x128 part.  Each
-  // wavefront passes one 32-row band at a time through its own LDS patch (fp32,
-  // padded rows) so that global memory sees 16-byte accesses along rows.
+  // wavefront passes sixteen rows at a time (registers 8 h .. 8 h + 7 of the four blocks of
+  // a 32-row band, h = 0, 1) through its own LDS patch (fp32, padded rows) so that global
+  // memory sees 16-byte accesses along rows.  The patch belongs to the wavefront alone and a
+  // wavefront's LDS accesses complete in order, so neither reusing the patch nor reading it
+  // back needs a workgroup barrier.
   // The lane and wavefront indices are taken afresh behind a compiler barrier: the addresses
   // below would otherwise be computed before the k loop and kept in scratch memory across it.
   {
@@ -622,7 +662,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   asm volatile("" : "+v"(lane_again), "+v"(wave_again));
   const int lane = lane_again, wave = wave_again;
   const int wm = wave >> 1, wn = wave & 1;
-  float* ep = (float*)(smem + wave * kEpWaveBytes);
+  float* ep = (float*)(smem + kEpBase + wave * kEpWaveBytes);
   const bf16_t* __restrict__ Gs = p.G;
   const bf16_t* __restrict__ Us = p.U;
   bf16_t* __restrict__ C0 = p.C0 + (MODE == MODE_DW ? (long)t.e * p.M * p.N : 0);
@@ -636,22 +676,23 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     desc[1] = t.m_end;
     desc[2] = t.n0;
   }
+  constexpr int kPasses = kEpRows / 4;  // 64 lanes cover 4 rows x 128 columns (gate/up: 8 rows x 64 + 64) per pass
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    // (the patch belongs to this wavefront alone and a wavefront's LDS accesses complete in
-    // order, so neither reusing the patch nor reading it back needs a workgroup barrier)
-    const int band_row = t.m0 + wm * 64 + i * 32;
-    // folded combine: the band's token indices, then (once the band's accumulators have left
-    // their registers) weights and residual rows, are requested all at once, so that their
+  for (int ih = 0; ih < 4; ++ih) {
+    const int i = ih >> 1, h = ih & 1;
+    const int tile_row = wm * 64 + i * 32 + h * kEpRows;  // first of the sixteen rows, inside the tile
+    const int band_row = t.m0 + tile_row;
+    // folded combine / scatter: the rows' token indices, then (once their accumulators have
+    // left the registers) weights and residual rows, are requested all at once, so that their
     // latencies overlap each other and the LDS pass (out may alias res: every element is
     // read and written by the same thread only)
-    int token[8];
-    float weight[8];
-    u32x4 resid[8];
+    int token[kPasses];
+    float weight[kPasses];
+    u32x4 resid[kPasses];
     const bool fold = FOLDS && !parted;
     if (fold) {
 #pragma unroll
-      for (int s = 0; s < 8; ++s) {
+      for (int s = 0; s < kPasses; ++s) {
         const int row = band_row + s * 4 + (lane >> 4);
         token[s] = row < t.m_end ? p.scatter[row] : p.scatter[t.m0];
       }
@@ -659,12 +700,12 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r)
-        ep[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * kEpPitch + j * 32 + (lane & 31)] = acc[i][j][r];
+      for (int r8 = 0; r8 < 8; ++r8)
+        ep[((r8 >> 2) * 8 + (lane >> 5) * 4 + (r8 & 3)) * kEpPitch + j * 32 + (lane & 31)] = acc[i][j][h * 8 + r8];
     if (fold) {
       const int col = t.n0 + wn * 128 + (lane & 15) * 8;
 #pragma unroll
-      for (int s = 0; s < 8; ++s) {
+      for (int s = 0; s < kPasses; ++s) {
         weight[s] = p.scale ? p.scale[token[s]] : 1.f;
         resid[s] = u32x4{0u, 0u, 0u, 0u};
         if (p.res && col < n_end) resid[s] = *(const u32x4*)(p.res + (long)token[s] * p.ldc + col);
@@ -673,7 +714,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     if (MODE == MODE_GATEUP) {
       // LDS row: 64 gate columns then the 64 matching up columns
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
+      for (int s = 0; s < kEpRows / 8; ++s) {
         const int rl = s * 8 + (lane >> 3), c0 = (lane & 7) * 8;
         const int row = band_row + rl, col = t.n0 + wn * 64 + c0;
         float g[8], u[8], a_[8];
@@ -692,7 +733,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
       }
     } else {
 #pragma unroll
-      for (int s = 0; s < 8; ++s) {
+      for (int s = 0; s < kPasses; ++s) {
         const int rl = s * 4 + (lane >> 4), c0 = (lane & 15) * 8;
         const int row = band_row + rl, col = t.n0 + wn * 128 + c0;
         const bool ok = row < t.m_end && col < n_end;
@@ -701,7 +742,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
 #pragma unroll
         for (int q = 0; q < 8; ++q) v[q] = ep[rl * kEpPitch + c0 + q];
         if (CAN_SPLIT && parted) {
-          float* dst = part + (wm * 64 + i * 32 + rl) * BN + wn * 128 + c0;
+          float* dst = part + (tile_row + rl) * BN + wn * 128 + c0;
           *(float4*)dst = make_float4(v[0], v[1], v[2], v[3]);
           *(float4*)(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
         } else if (MODE == MODE_DA) {
@@ -729,7 +770,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     }
   }
   }
-  __syncthreads();  // the LDS patches are reused by the next tile's staging
+  __syncthreads();  // the LDS patches overlap stage 1, which the next tile's second k tile goes to
   }  // tile loop
 }
 
