@@ -41,7 +41,7 @@
 namespace dynmo {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
-typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 typedef __attribute__((ext_vector_type(8))) short s16x8_t;
 
@@ -51,7 +51,7 @@ constexpr int kWaves = kMfmaThreads / 64;
 constexpr int kPieces = 32 / kWaves;           // 1 KB pieces of an operand tile per wavefront
 constexpr int kTileBytes = 256 * 64 * 2;       // one operand tile (256 rows x 64 k, bf16), unpadded
 constexpr int kStageBytes = 2 * kTileBytes;    // A then B
-constexpr int kEpPitch = 136;                  // floats per row of an epilogue LDS patch (128 + 8 pad)
+constexpr int kEpPitch = 132;                  // floats per row of an epilogue LDS patch (128 + 4: rows 4 apart are 16 banks apart)
 constexpr int kEpRows = 16;                    // rows a wavefront passes through its patch at a time
 constexpr int kEpWaveBytes = kEpRows * kEpPitch * 4;
 // The epilogue patches lie behind stage 0, which is free while they are in use: the next
@@ -118,7 +118,8 @@ struct GemmParams {
 //   [row][k]: 128 bytes per row; the 16-byte piece with k = 8 c .. 8 c + 7 of row r sits at
 //             r * 128 + ((c ^ ((r >> 1) & 7)) << 4)
 //   [k][row]: 512 bytes per k-row in eight 64-byte blocks of 32 rows; block b of k-row k
-//             sits at k * 512 + (((b & 4) | ((b ^ k) & 3)) << 6)
+//             sits at k * 512 + (((b & 4) | ((b ^ k) & 3)) << 6), and its two 32-byte halves
+//             (16 rows each) are swapped when bit 3 of k is set
 constexpr uint32_t kOob = 0x80000000u;
 
 // raw buffer descriptor (wave-uniform): base address, stride 0, record count in bytes
@@ -189,7 +190,8 @@ __device__ __forceinline__ Pieces pieces_rowk(uint32_t ld_bytes, int rows_left, 
 }
 
 // [k][row] memory: piece q holds k-rows 2 q and 2 q + 1; lane l fills 16-byte slot l % 32 of
-// k-row 2 q + l / 32, i.e. quarter (l % 4) of stored block (l % 32) / 4.
+// k-row 2 q + l / 32, i.e. quarter (l % 4) of stored block (l % 32) / 4 (quarters 0, 1 and
+// 2, 3 are the block's two halves).
 __device__ __forceinline__ Pieces pieces_krow(uint32_t ld_bytes, int rows_left) {
   Pieces ps;
   const int tid = tid_now();
@@ -199,7 +201,8 @@ __device__ __forceinline__ Pieces pieces_krow(uint32_t ld_bytes, int rows_left) 
     const int k = (wave * kPieces + j) * 2 + (lane >> 5);
     const int slot = lane & 31, stored = slot >> 2;
     const int blk = (stored & 4) | ((stored ^ k) & 3);
-    const int col = blk * 32 + (slot & 3) * 8;
+    const int quarter = (slot & 3) ^ (((k >> 3) & 1) << 1);
+    const int col = blk * 32 + quarter * 8;
     ps.off[j] = col < rows_left ? (uint32_t)k * ld_bytes + col * 2 : kOob;
     ps.kpos[j] = k;
   }
@@ -226,59 +229,86 @@ __device__ __forceinline__ Pieces pieces_rowk_gather(uint32_t ld_bytes, int row0
 }
 
 // ---- LDS -> MFMA operand fragments ---------------------------------------------
-// Operand of v_mfma_f32_32x32x16_bf16: lane l holds, for row (l % 32) of the 32-row
-// block, the eight k values (l / 32) * 8 .. + 7 of the 16-wide k step.
+// Operand of v_mfma_f32_16x16x32_bf16: lane l holds, for row (l % 16) of the 16-row
+// block, the eight k values (l / 16) * 8 .. + 7 of the 32-wide k step.
 //
 // Per-lane byte addresses (inside an operand tile) from which every fragment of a k tile is
-// reached by adding a compile-time constant.  [row][k] tiles: one address per k step (the
-// swizzle mixes the k piece into the address; the 32-row block adds block * 4096).
+// reached by a compile-time constant.  [row][k] tiles: one address per 32-wide k step (the
+// swizzle mixes the k piece into the address; the 16-row block adds block * 2048).
 // [k][row] tiles: one address per 32-row block (the swizzle mixes the block into the
-// address; the k step adds step * 16 * 512).  `first_block` is the wavefront's first block;
-// `block_of[i]` the i-th block it reads, relative to it.
+// address; its second 16 rows are reached by flipping bit 5, the k step adds step * 32 * 512).
+// `first16` is the wavefront's first 16-row block; it is even.
 struct FragAddr {
   uint32_t a[4];
 };
 
 template <bool TRANS>
-__device__ __forceinline__ FragAddr frag_addr(int first_block, const int (&block_of)[4]) {
+__device__ __forceinline__ FragAddr frag_addr(int first16) {
   FragAddr fa;
   const int lane = tid_now() & 63;
+  const int s = lane & 15, g = lane >> 4;
   if (!TRANS) {
-    const int r = lane & 31, h = lane >> 5;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-      fa.a[ks] = (uint32_t)((first_block * 32 + r) * 128 + (((ks * 2 + h) ^ ((r >> 1) & 7)) << 4));
+    for (int h = 0; h < 2; ++h) fa.a[h] = (uint32_t)((first16 * 16 + s) * 128 + (((h * 4 + g) ^ ((s >> 1) & 7)) << 4));
+    fa.a[2] = fa.a[3] = 0;
   } else {
     // ds_read_b64_tr_b16 works on groups of 16 lanes: lane s of a group points at four
     // consecutive rows (s % 4) * 4 .. + 3 of k-row (s / 4); afterwards lane i of the group
-    // holds row i for those four k-rows.
-    const int s = lane & 15, h = lane >> 5;
-    const int k = h * 8 + (s >> 2);
+    // holds row i for those four k-rows.  Group g reads k-rows 8 g .. 8 g + 7 (two reads).
+    const int k = g * 8 + (s >> 2);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int blk = first_block + block_of[i];
+      const int blk = (first16 >> 1) + i;
       const int stored = (blk & 4) | ((blk ^ k) & 3);
-      fa.a[i] = (uint32_t)(k * 512 + stored * 64 + (((lane >> 4) & 1) * 16 + (s & 3) * 4) * 2);
+      fa.a[i] = (uint32_t)(k * 512 + stored * 64 + ((g & 1) << 5) + (s & 3) * 8);
     }
   }
   return fa;
 }
 
-// Fragment `i` (the i-th block the wavefront reads, at relative block BLK) of k step KS.
-template <bool TRANS, int BLK, int KS>
-__device__ __forceinline__ bf16x8_t lfrag(const char* tile, const FragAddr& fa, int i) {
-  if (!TRANS) {
-    return *(const bf16x8_t*)(tile + fa.a[KS] + BLK * 4096);
-  } else {
-    typedef __attribute__((address_space(3))) s16x4_t* lds_ptr;
-    const char* q = tile + fa.a[i] + KS * 16 * 512;
-    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)q);
-    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(q + 4 * 512));
-    s16x8_t v;
-    v.s0 = lo.x; v.s1 = lo.y; v.s2 = lo.z; v.s3 = lo.w;
-    v.s4 = hi.x; v.s5 = hi.y; v.s6 = hi.z; v.s7 = hi.w;
-    return __builtin_bit_cast(bf16x8_t, v);
+// A fragment in registers: one 16-byte LDS read for [row][k] tiles, two transposing 8-byte
+// reads for [k][row] tiles.
+template <bool TRANS>
+struct Frag {
+  bf16x8_t v;
+  __device__ __forceinline__ bf16x8_t operand() const { return v; }
+};
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+template <>
+struct Frag<true> {
+  u32x2_t lo, hi;
+  __device__ __forceinline__ bf16x8_t operand() const {
+    return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3));
   }
+};
+template <bool TRANS>
+constexpr int kReadsPerFrag = TRANS ? 2 : 1;
+
+// Reads the fragment of the wavefront's 16-row block N16 (relative to its first one) for the
+// 32-wide k step H from the operand tile at LDS offset `tile` (+ TILE_OFF) into `f`.  Written
+// as assembly with the fragment as an in-out operand: the new value then takes the registers
+// of the old one (left to itself the compiler gives every read of the unrolled k tile fresh
+// registers, twice the fragments' share of the file, and spills loop invariants instead).
+// The compiler therefore does not know these reads; wait_frag() below stands in for its waits.
+template <bool TRANS, int N16, int H, int TILE_OFF>
+__device__ __forceinline__ void read_frag(Frag<TRANS>& f, uint32_t tile, const FragAddr& fa) {
+  if constexpr (!TRANS) {
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "+v"(f.v) : "v"(tile + fa.a[H]), "n"(TILE_OFF + N16 * 2048) : "memory");
+  } else {
+    const uint32_t q = tile + (fa.a[N16 >> 1] ^ ((N16 & 1) << 5));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "+v"(f.lo) : "v"(q), "n"(TILE_OFF + H * 32 * 512) : "memory");
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "+v"(f.hi) : "v"(q), "n"(TILE_OFF + H * 32 * 512 + 4 * 512) : "memory");
+  }
+}
+
+// Waits until at most N of this wavefront's LDS reads are outstanding (they complete in
+// order); `f` is the fragment the next MFMA is waiting for, named so that the MFMA cannot be
+// moved in front of the wait.
+template <int N, bool TRANS>
+__device__ __forceinline__ void wait_frag(Frag<TRANS>& f) {
+  constexpr int n = N < 15 ? N : 15;
+  if constexpr (!TRANS) asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(f.v) : "n"(n));
+  else asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(f.lo), "+v"(f.hi) : "n"(n));
 }
 
 // ---- tile schedule ---------------------------------------------------------------
@@ -514,55 +544,59 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm = wave >> 1, wn = wave & 1;  // 4 x 2 wavefronts, 64 x 128 outputs each
 
-  f32x16_t acc[2][4];
+  f32x4_t acc[4][8];  // 16 x 16 blocks: block (i, j) = rows 16 i .., columns 16 j .. of the wavefront's part
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 8; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
 
   // ---- main loop -------------------------------------------------------------
   // A hand-ordered software pipeline; __builtin_amdgcn_sched_barrier(0) after every
   // MFMA slot keeps the compiler from regrouping it.  Tile kt is in LDS stage kt % 2 and
-  // the pieces of tile kt + 1 are in flight to the other stage on entry.  Each of the
-  // four 16-wide k steps issues 8 MFMAs on fragments that were read during the step before:
-  //   step 0: MFMAs | fragment reads for step 1
-  //   step 1: MFMAs | fragment reads for step 2
-  //   step 2: MFMAs | fragment reads for step 3
+  // the pieces of tile kt + 1 are in flight to the other stage on entry.  A k tile is two
+  // 32-wide k steps of 32 MFMAs (4 row blocks x 8 column blocks, row-major).  Every fragment
+  // has one register set and is replaced as soon as its last MFMA of the step has been issued
+  // (an A fragment after its row, a B fragment in row 3), at least eight MFMA slots before it
+  // is needed again:
+  //   step 0: MFMAs | fragments of step 1 as their registers fall free
+  //   step 1, row 0: MFMAs
   //   wait for this wavefront's pieces of tile kt + 1 and for its LDS reads; barrier:
   //   now tile kt + 1 is complete and nobody reads the stage of tile kt any more
-  //   step 3: MFMAs | fragment reads for step 0 of tile kt + 1, and one piece of tile
-  //           kt + 2 per MFMA into the stage of tile kt
+  //   step 1, rows 1..3: MFMAs | fragments of step 0 of tile kt + 1 as their registers fall
+  //           free; one piece of tile kt + 2 every third MFMA into the stage of tile kt
   // so LDS latency is covered by MFMAs in flight (and by the SIMD's other wavefront), a
   // piece has a whole k tile to land, and the memory instructions are spread out: a burst
   // of them would hold up the wavefront's own MFMAs.  Past the last tile the loads are
   // masked (zeros, no memory access), which keeps the loop body free of branches.
-  bf16x8_t fa[2][2], fb[2][4];
+  Frag<A_TRANS> fa[4];
+  Frag<B_TRANS> fb[8];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) fa[i] = Frag<A_TRANS>{};
+#pragma unroll
+  for (int j = 0; j < 8; ++j) fb[j] = Frag<B_TRANS>{};
+  constexpr int RA = kReadsPerFrag<A_TRANS>, RB = kReadsPerFrag<B_TRANS>;
   const Pieces pa = pieces_a(t), pb = pieces_b(t);
-  // the 32-row blocks this wavefront reads: two of A, four of B (gate/up: two gate blocks and the two matching up blocks)
-  constexpr int kBlocksA[4] = {0, 1, 0, 0};
-  constexpr int kBlocksB[4] = {0, 1, MODE == MODE_GATEUP ? 4 : 2, MODE == MODE_GATEUP ? 5 : 3};
-  const FragAddr fra = frag_addr<A_TRANS>((wave_u >> 1) * 2, kBlocksA);
-  const FragAddr frb = frag_addr<B_TRANS>(MODE == MODE_GATEUP ? (wave_u & 1) * 2 : (wave_u & 1) * 4, kBlocksB);
+  // first 16-row block of this wavefront in each operand tile (gate/up: 64 gate rows, and the 64 matching up rows 128 further on)
+  const FragAddr fra = frag_addr<A_TRANS>((wave_u >> 1) * 4);
+  const FragAddr frb = frag_addr<B_TRANS>(MODE == MODE_GATEUP ? (wave_u & 1) * 4 : (wave_u & 1) * 8);
   auto ktile = [&](int kt) { return ktile_of(t, kr, kt); };
-  // fragment f of k step KS: 0..1 = row blocks of A, 2..5 = column blocks of B
-  auto read_frag = [&](auto BUF, auto F, const char* stage, auto KS) {
-    constexpr int Q = decltype(BUF)::value, f = decltype(F)::value, ks = decltype(KS)::value;
-    if constexpr (f < 2) {
-      fa[Q][f] = lfrag<A_TRANS, kBlocksA[f], ks>(stage, fra, f);
-    } else {
-      constexpr int j = f - 2;
-      fb[Q][j] = lfrag<B_TRANS, kBlocksB[j], ks>(stage + kTileBytes, frb, j);
-    }
+  // A fragment of row block I / B fragment of column block J for k step H
+  auto read_a = [&](auto I, uint32_t stage, auto H) {
+    read_frag<A_TRANS, decltype(I)::value, decltype(H)::value, 0>(fa[decltype(I)::value], stage, fra);
   };
-  auto mfma = [&](auto BUF, auto M) {
-    constexpr int Q = decltype(BUF)::value, i = decltype(M)::value >> 2, j = decltype(M)::value & 3;
-    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[Q][i], fb[Q][j], acc[i][j], 0, 0, 0);
+  auto read_b = [&](auto J, uint32_t stage, auto H) {
+    constexpr int j = decltype(J)::value;
+    constexpr int n16 = MODE == MODE_GATEUP ? (j & 3) + (j >> 2) * 8 : j;
+    read_frag<B_TRANS, n16, decltype(H)::value, kTileBytes>(fb[j], stage, frb);
+  };
+  auto mfma = [&](auto I, auto J) {
+    constexpr int i = decltype(I)::value, j = decltype(J)::value;
+    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i].operand(), fb[j].operand(), acc[i][j], 0, 0, 0);
   };
   const std::integral_constant<int, 0> c0;
   const std::integral_constant<int, 1> c1;
-  const std::integral_constant<int, 2> c2;
   const std::integral_constant<int, 3> c3;
 
   if (!first_in_flight) {
@@ -592,46 +626,70 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
       static_for<kPieces>([&](auto J) { dma_a(pa, q2, freed, J); });
       static_for<kPieces>([&](auto J) { dma_b(pb, q2, freed, J); });
     }
-  } else {
-  static_for<6>([&](auto F) { read_frag(c0, F, smem, c0); });
-
-  for (int kt = kt_lo; kt < kt_hi; ++kt) {
-    const int stage = (kt - kt_lo) & 1;
-    const char* cur = smem + stage * kStageBytes;
-    const char* next = smem + (stage ^ 1) * kStageBytes;
-    const uint32_t freed = lds0 + stage * kStageBytes;
-    const KTile q2 = ktile(kt + 2);
+  } else if (kt_lo < kt_hi) {  // (an expert without rows has nothing to contract: its tiles of MODE_DW stay zero)
+  // Order of a step's fragment reads: A 0, 1, 2 (each after its row), B 0 .. 7 (row 3), A 3.
+  // Reads complete in order, so what a MFMA has to wait for is the number of reads issued
+  // after its youngest fragment: B j of the step before is followed by B j+1 .. 7 and A 3.
+  static_for<3>([&](auto I) { read_a(I, lds0, c0); });
+  static_for<8>([&](auto J) { read_b(J, lds0, c0); });
+  read_a(c3, lds0, c0);
+  // row 0 of a step: every MFMA waits for its B fragment
+  auto row0 = [&]() {
+    static_for<8>([&](auto J) {
+      wait_frag<(7 - decltype(J)::value) * RB + RA>(fb[decltype(J)::value]);
+      mfma(c0, J);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+  };
+  // The loop is rotated so that its body starts right behind the barrier.
+  auto step0 = [&](uint32_t cur) {
+    row0();
+    read_a(c0, cur, c1);
     __builtin_amdgcn_sched_barrier(0);
-    // step 0: fragments of step 1 go to buffer 1
-    static_for<8>([&](auto M) {
-      if constexpr (M < 6) read_frag(c1, M, cur, c1);
-      mfma(c0, M);
+    static_for<24>([&](auto M) {
+      constexpr int m = decltype(M)::value, i = 1 + (m >> 3), j = m & 7;
+      if constexpr (m == 16) wait_frag<3 * RA>(fa[3]);  // A 3 of this step is followed by A 0, 1, 2 of the next
+      mfma(std::integral_constant<int, i>{}, std::integral_constant<int, j>{});
+      if constexpr (i == 3) read_b(std::integral_constant<int, j>{}, cur, c1);
+      if constexpr (j == 7) read_a(std::integral_constant<int, i>{}, cur, c1);
       __builtin_amdgcn_sched_barrier(0);
     });
-    // step 1
-    static_for<8>([&](auto M) {
-      if constexpr (M < 6) read_frag(c0, M, cur, c2);
-      mfma(c1, M);
-      __builtin_amdgcn_sched_barrier(0);
-    });
-    // step 2
-    static_for<8>([&](auto M) {
-      if constexpr (M < 6) read_frag(c1, M, cur, c3);
-      mfma(c0, M);
-      __builtin_amdgcn_sched_barrier(0);
-    });
+  };
+  auto step1_row0_and_barrier = [&]() {
+    row0();
     wait_loads_and_lds();
     wg_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    // step 3: the next tile's first fragments, and the refill of the stage just freed
-    static_for<8>([&](auto M) {
-      if constexpr (M < 6) read_frag(c0, M, next, c0);
-      if constexpr (M < kPieces) dma_a(pa, q2, freed, M);
-      else dma_b(pb, q2, freed, M - kPieces);
-      mfma(c1, M);
+  };
+  // rows 1..3 of step 1; REFILL: with the next tile's first fragments and the refill of the stage just freed
+  auto step1_rest = [&](auto REFILL, uint32_t next, uint32_t freed, const KTile& q2) {
+    constexpr bool refill = decltype(REFILL)::value != 0;
+    if constexpr (refill) read_a(c0, next, c0);
+    static_for<24>([&](auto M) {
+      constexpr int m = decltype(M)::value, i = 1 + (m >> 3), j = m & 7;
+      if constexpr (refill && m % 3 == 0) {
+        constexpr int piece = m / 3;
+        if constexpr (piece < kPieces) dma_a(pa, q2, freed, piece);
+        else dma_b(pb, q2, freed, piece - kPieces);
+      }
+      mfma(std::integral_constant<int, i>{}, std::integral_constant<int, j>{});
+      if constexpr (refill && i == 3) read_b(std::integral_constant<int, j>{}, next, c0);
+      if constexpr (refill && j == 7) read_a(std::integral_constant<int, i>{}, next, c0);
       __builtin_amdgcn_sched_barrier(0);
     });
+  };
+  __builtin_amdgcn_sched_barrier(0);
+  step0(lds0);
+  step1_row0_and_barrier();
+  for (int kt = kt_lo; kt + 1 < kt_hi; ++kt) {
+    const int stage = (kt - kt_lo) & 1;
+    const uint32_t next = lds0 + (stage ^ 1) * kStageBytes;
+    const KTile q2 = ktile(kt + 2);
+    step1_rest(c1, next, lds0 + stage * kStageBytes, q2);
+    step0(next);
+    step1_row0_and_barrier();
   }
+  step1_rest(c0, lds0, lds0, KTile{});
   }  // has_work
   // every piece (masked ones included) has landed and nobody reads the stages any more
   wait_loads_and_lds();
@@ -648,11 +706,10 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     static_for<kPieces>([&](auto J) { dma_b(pbn, qn, lds0, J); });
   }
 
-  // ---- epilogue.  Accumulator element r of block (i, j) is row i*32 + (r/4)*8 +
-  // (lane/32)*4 + r%4, column j*32 + lane%32 of the wavefront's 64x128 part.  Each
-  // wavefront passes sixteen rows at a time (registers 8 h .. 8 h + 7 of the four blocks of
-  // a 32-row band, h = 0, 1) through its own LDS patch (fp32, padded rows) so that global
-  // memory sees 16-byte accesses along rows.  The patch belongs to the wavefront alone and a
+  // ---- epilogue.  Accumulator element r of block (i, j) is row 16 i + (lane/16)*4 + r,
+  // column 16 j + lane%16 of the wavefront's 64x128 part.  Each wavefront passes sixteen
+  // rows at a time (the eight blocks of row block i) through its own LDS patch (fp32, padded
+  // rows) so that global memory sees 16-byte accesses along rows.  The patch belongs to the wavefront alone and a
   // wavefront's LDS accesses complete in order, so neither reusing the patch nor reading it
   // back needs a workgroup barrier.
   // The lane and wavefront indices are taken afresh behind a compiler barrier: the addresses
@@ -678,9 +735,8 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   }
   constexpr int kPasses = kEpRows / 4;  // 64 lanes cover 4 rows x 128 columns (gate/up: 8 rows x 64 + 64) per pass
 #pragma unroll
-  for (int ih = 0; ih < 4; ++ih) {
-    const int i = ih >> 1, h = ih & 1;
-    const int tile_row = wm * 64 + i * 32 + h * kEpRows;  // first of the sixteen rows, inside the tile
+  for (int i = 0; i < 4; ++i) {
+    const int tile_row = wm * 64 + i * kEpRows;  // first of the sixteen rows, inside the tile
     const int band_row = t.m0 + tile_row;
     // folded combine / scatter: the rows' token indices, then (once their accumulators have
     // left the registers) weights and residual rows, are requested all at once, so that their
@@ -698,10 +754,9 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
       }
     }
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 8; ++j)
 #pragma unroll
-      for (int r8 = 0; r8 < 8; ++r8)
-        ep[((r8 >> 2) * 8 + (lane >> 5) * 4 + (r8 & 3)) * kEpPitch + j * 32 + (lane & 31)] = acc[i][j][h * 8 + r8];
+      for (int r = 0; r < 4; ++r) ep[((lane >> 4) * 4 + r) * kEpPitch + j * 16 + (lane & 15)] = acc[i][j][r];
     if (fold) {
       const int col = t.n0 + wn * 128 + (lane & 15) * 8;
 #pragma unroll
