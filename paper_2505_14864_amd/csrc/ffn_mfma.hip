@@ -129,7 +129,7 @@ __device__ __forceinline__ desc_t make_desc(const bf16_t* p, uint32_t bytes) {
   desc_t d;
   d.x = (uint32_t)a;
   d.y = (uint32_t)(a >> 32) & 0xffffu;
-  d.z = bytes;
+  d.z = __builtin_amdgcn_readfirstlane(bytes);
   d.w = 0x00020000u;
   return d;
 }
@@ -232,35 +232,40 @@ __device__ __forceinline__ Pieces pieces_rowk_gather(uint32_t ld_bytes, int row0
 // Operand of v_mfma_f32_16x16x32_bf16: lane l holds, for row (l % 16) of the 16-row
 // block, the eight k values (l / 16) * 8 .. + 7 of the 32-wide k step.
 //
-// Per-lane byte addresses (inside an operand tile) from which every fragment of a k tile is
+// Per-lane LDS addresses (of the stage being read) from which every fragment of a k tile is
 // reached by a compile-time constant.  [row][k] tiles: one address per 32-wide k step (the
 // swizzle mixes the k piece into the address; the 16-row block adds block * 2048).
-// [k][row] tiles: one address per 32-row block (the swizzle mixes the block into the
-// address; its second 16 rows are reached by flipping bit 5, the k step adds step * 32 * 512).
-// `first16` is the wavefront's first 16-row block; it is even.
+// [k][row] tiles: one address per 16-row block (the swizzle mixes the block into the address;
+// the k step adds step * 32 * 512).  `first16` is the wavefront's first 16-row block; it is even.
+// The k loop moves the addresses from stage to stage in place (shift()).
+template <bool TRANS, int BLOCKS>
 struct FragAddr {
-  uint32_t a[4];
+  static constexpr int kCount = TRANS ? BLOCKS : 2;
+  uint32_t a[kCount];
+  __device__ __forceinline__ void shift(uint32_t delta) {
+#pragma unroll
+    for (int i = 0; i < kCount; ++i) a[i] += delta;
+  }
 };
 
-template <bool TRANS>
-__device__ __forceinline__ FragAddr frag_addr(int first16) {
-  FragAddr fa;
+template <bool TRANS, int BLOCKS>
+__device__ __forceinline__ FragAddr<TRANS, BLOCKS> frag_addr(uint32_t stage, int first16) {
+  FragAddr<TRANS, BLOCKS> fa;
   const int lane = tid_now() & 63;
   const int s = lane & 15, g = lane >> 4;
-  if (!TRANS) {
+  if constexpr (!TRANS) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) fa.a[h] = (uint32_t)((first16 * 16 + s) * 128 + (((h * 4 + g) ^ ((s >> 1) & 7)) << 4));
-    fa.a[2] = fa.a[3] = 0;
+    for (int h = 0; h < 2; ++h) fa.a[h] = stage + (uint32_t)((first16 * 16 + s) * 128 + (((h * 4 + g) ^ ((s >> 1) & 7)) << 4));
   } else {
     // ds_read_b64_tr_b16 works on groups of 16 lanes: lane s of a group points at four
     // consecutive rows (s % 4) * 4 .. + 3 of k-row (s / 4); afterwards lane i of the group
     // holds row i for those four k-rows.  Group g reads k-rows 8 g .. 8 g + 7 (two reads).
     const int k = g * 8 + (s >> 2);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int blk = (first16 >> 1) + i;
+    for (int n = 0; n < BLOCKS; ++n) {
+      const int blk = (first16 + n) >> 1, half = (first16 + n) & 1;
       const int stored = (blk & 4) | ((blk ^ k) & 3);
-      fa.a[i] = (uint32_t)(k * 512 + stored * 64 + ((g & 1) << 5) + (s & 3) * 8);
+      fa.a[n] = stage + (uint32_t)(k * 512 + stored * 64 + (((g & 1) ^ half) << 5) + (s & 3) * 8);
     }
   }
   return fa;
@@ -285,19 +290,18 @@ template <bool TRANS>
 constexpr int kReadsPerFrag = TRANS ? 2 : 1;
 
 // Reads the fragment of the wavefront's 16-row block N16 (relative to its first one) for the
-// 32-wide k step H from the operand tile at LDS offset `tile` (+ TILE_OFF) into `f`.  Written
+// 32-wide k step H into `f`; TILE_OFF = the operand tile's offset inside a stage.  Written
 // as assembly with the fragment as an in-out operand: the new value then takes the registers
 // of the old one (left to itself the compiler gives every read of the unrolled k tile fresh
 // registers, twice the fragments' share of the file, and spills loop invariants instead).
 // The compiler therefore does not know these reads; wait_frag() below stands in for its waits.
-template <bool TRANS, int N16, int H, int TILE_OFF>
-__device__ __forceinline__ void read_frag(Frag<TRANS>& f, uint32_t tile, const FragAddr& fa) {
+template <bool TRANS, int N16, int H, int TILE_OFF, int BLOCKS>
+__device__ __forceinline__ void read_frag(Frag<TRANS>& f, const FragAddr<TRANS, BLOCKS>& fa) {
   if constexpr (!TRANS) {
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "+v"(f.v) : "v"(tile + fa.a[H]), "n"(TILE_OFF + N16 * 2048) : "memory");
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "+v"(f.v) : "v"(fa.a[H]), "n"(TILE_OFF + N16 * 2048) : "memory");
   } else {
-    const uint32_t q = tile + (fa.a[N16 >> 1] ^ ((N16 & 1) << 5));
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "+v"(f.lo) : "v"(q), "n"(TILE_OFF + H * 32 * 512) : "memory");
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "+v"(f.hi) : "v"(q), "n"(TILE_OFF + H * 32 * 512 + 4 * 512) : "memory");
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "+v"(f.lo) : "v"(fa.a[N16]), "n"(TILE_OFF + H * 32 * 512) : "memory");
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "+v"(f.hi) : "v"(fa.a[N16]), "n"(TILE_OFF + H * 32 * 512 + 4 * 512) : "memory");
   }
 }
 
@@ -416,7 +420,9 @@ __device__ __forceinline__ void static_for(F&& f) {
 
 __device__ __forceinline__ float silu_mul(float g, float u) { return g * sigmoidf_(g) * u; }
 
-template <int MODE>
+// WHOLE_K: the contraction length is a multiple of the k tile, so the [row][k] operands need no
+// per-lane k mask (the [k][row] operands never do: their k range is the buffer's record count).
+template <int MODE, bool WHOLE_K>
 __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmParams p) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr bool A_TRANS = MODE == MODE_DW;
@@ -516,16 +522,25 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     const bf16_t* A = ph == 0 ? p.A1 : p.A2;
     const bf16_t* Bw = ((IS_DX && ph == 1) || second_b) ? p.B2 : p.B1;
     const bf16_t* B = Bw + (MODE == MODE_DW ? 0 : (long)tt.e * p.b_expert_stride);
-    q.a = make_desc(A_TRANS ? A + (long)k0 * p.lda + tt.m0 : A + (gathered ? 0 : (long)tt.m0 * p.lda) + k0, 0x7ffffffeu);
-    q.b = make_desc(B_TRANS ? B + (long)k0 * p.ldb + tt.n0 : B + (long)tt.n0 * p.ldb + k0, 0x7ffffffeu);
+    // record counts: nothing past the k range is fetched (zeros land in LDS instead); a [k][row]
+    // operand's k-rows are whole records, so its count is also the k mask of a ragged last tile
+    // (k_left is the same in every lane, which the compiler cannot see: it comes out of the LDS table)
+    const int k_left_u = __builtin_amdgcn_readfirstlane(q.k_left);
+    const uint32_t k_rows = (uint32_t)max(0, min(k_left_u, BK));
+    const uint32_t any = k_left_u > 0 ? 0x7ffffffeu : 0u;
+    q.a = make_desc(A_TRANS ? A + (long)k0 * p.lda + tt.m0 : A + (gathered ? 0 : (long)tt.m0 * p.lda) + k0,
+                    A_TRANS ? k_rows * lda_b : any);
+    q.b = make_desc(B_TRANS ? B + (long)k0 * p.ldb + tt.n0 : B + (long)tt.n0 * p.ldb + k0, B_TRANS ? k_rows * ldb_b : any);
     return q;
   };
   // this wavefront's pieces of k tile q (pieces pa / pb) into the stage at LDS offset `stage`
   auto dma_a = [&](const Pieces& pa, const KTile& q, uint32_t stage, int j) {
-    load_to_lds(q.a, stage + (wave_u * kPieces + j) * 1024, pa.kpos[j] < q.k_left ? pa.off[j] : kOob);
+    load_to_lds(q.a, stage + (wave_u * kPieces + j) * 1024,
+                A_TRANS || WHOLE_K || pa.kpos[j] < q.k_left ? pa.off[j] : kOob);
   };
   auto dma_b = [&](const Pieces& pb, const KTile& q, uint32_t stage, int j) {
-    load_to_lds(q.b, stage + kTileBytes + (wave_u * kPieces + j) * 1024, pb.kpos[j] < q.k_left ? pb.off[j] : kOob);
+    load_to_lds(q.b, stage + kTileBytes + (wave_u * kPieces + j) * 1024,
+                B_TRANS || WHOLE_K || pb.kpos[j] < q.k_left ? pb.off[j] : kOob);
   };
   const int n_rounds = my_rounds + (has_part ? 1 : 0);
   auto tile_at = [&](int round) {
@@ -579,17 +594,18 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   constexpr int RA = kReadsPerFrag<A_TRANS>, RB = kReadsPerFrag<B_TRANS>;
   const Pieces pa = pieces_a(t), pb = pieces_b(t);
   // first 16-row block of this wavefront in each operand tile (gate/up: 64 gate rows, and the 64 matching up rows 128 further on)
-  const FragAddr fra = frag_addr<A_TRANS>((wave_u >> 1) * 4);
-  const FragAddr frb = frag_addr<B_TRANS>(MODE == MODE_GATEUP ? (wave_u & 1) * 4 : (wave_u & 1) * 8);
+  FragAddr<A_TRANS, 4> fra = frag_addr<A_TRANS, 4>(lds0, (wave_u >> 1) * 4);
+  FragAddr<B_TRANS, 8> frb = frag_addr<B_TRANS, 8>(lds0, MODE == MODE_GATEUP ? (wave_u & 1) * 4 : (wave_u & 1) * 8);
   auto ktile = [&](int kt) { return ktile_of(t, kr, kt); };
   // A fragment of row block I / B fragment of column block J for k step H
-  auto read_a = [&](auto I, uint32_t stage, auto H) {
-    read_frag<A_TRANS, decltype(I)::value, decltype(H)::value, 0>(fa[decltype(I)::value], stage, fra);
+  // (the stage read is the one fra / frb point into)
+  auto read_a = [&](auto I, auto H) {
+    read_frag<A_TRANS, decltype(I)::value, decltype(H)::value, 0>(fa[decltype(I)::value], fra);
   };
-  auto read_b = [&](auto J, uint32_t stage, auto H) {
+  auto read_b = [&](auto J, auto H) {
     constexpr int j = decltype(J)::value;
     constexpr int n16 = MODE == MODE_GATEUP ? (j & 3) + (j >> 2) * 8 : j;
-    read_frag<B_TRANS, n16, decltype(H)::value, kTileBytes>(fb[j], stage, frb);
+    read_frag<B_TRANS, n16, decltype(H)::value, kTileBytes>(fb[j], frb);
   };
   auto mfma = [&](auto I, auto J) {
     constexpr int i = decltype(I)::value, j = decltype(J)::value;
@@ -630,9 +646,9 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   // Order of a step's fragment reads: A 0, 1, 2 (each after its row), B 0 .. 7 (row 3), A 3.
   // Reads complete in order, so what a MFMA has to wait for is the number of reads issued
   // after its youngest fragment: B j of the step before is followed by B j+1 .. 7 and A 3.
-  static_for<3>([&](auto I) { read_a(I, lds0, c0); });
-  static_for<8>([&](auto J) { read_b(J, lds0, c0); });
-  read_a(c3, lds0, c0);
+  static_for<3>([&](auto I) { read_a(I, c0); });
+  static_for<8>([&](auto J) { read_b(J, c0); });
+  read_a(c3, c0);
   // row 0 of a step: every MFMA waits for its B fragment
   auto row0 = [&]() {
     static_for<8>([&](auto J) {
@@ -642,16 +658,16 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     });
   };
   // The loop is rotated so that its body starts right behind the barrier.
-  auto step0 = [&](uint32_t cur) {
+  auto step0 = [&]() {
     row0();
-    read_a(c0, cur, c1);
+    read_a(c0, c1);
     __builtin_amdgcn_sched_barrier(0);
     static_for<24>([&](auto M) {
       constexpr int m = decltype(M)::value, i = 1 + (m >> 3), j = m & 7;
       if constexpr (m == 16) wait_frag<3 * RA>(fa[3]);  // A 3 of this step is followed by A 0, 1, 2 of the next
       mfma(std::integral_constant<int, i>{}, std::integral_constant<int, j>{});
-      if constexpr (i == 3) read_b(std::integral_constant<int, j>{}, cur, c1);
-      if constexpr (j == 7) read_a(std::integral_constant<int, i>{}, cur, c1);
+      if constexpr (i == 3) read_b(std::integral_constant<int, j>{}, c1);
+      if constexpr (j == 7) read_a(std::integral_constant<int, i>{}, c1);
       __builtin_amdgcn_sched_barrier(0);
     });
   };
@@ -661,10 +677,15 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     wg_barrier();
     __builtin_amdgcn_sched_barrier(0);
   };
-  // rows 1..3 of step 1; REFILL: with the next tile's first fragments and the refill of the stage just freed
-  auto step1_rest = [&](auto REFILL, uint32_t next, uint32_t freed, const KTile& q2) {
+  // Rows 1..3 of step 1.  REFILL: with the next tile's first fragments (fra / frb move on to its
+  // stage) and the refill of the stage just freed.
+  auto step1_rest = [&](auto REFILL, uint32_t to_next, uint32_t freed, const KTile& q2) {
     constexpr bool refill = decltype(REFILL)::value != 0;
-    if constexpr (refill) read_a(c0, next, c0);
+    if constexpr (refill) {
+      fra.shift(to_next);
+      frb.shift(to_next);
+      read_a(c0, c0);
+    }
     static_for<24>([&](auto M) {
       constexpr int m = decltype(M)::value, i = 1 + (m >> 3), j = m & 7;
       if constexpr (refill && m % 3 == 0) {
@@ -673,23 +694,23 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
         else dma_b(pb, q2, freed, piece - kPieces);
       }
       mfma(std::integral_constant<int, i>{}, std::integral_constant<int, j>{});
-      if constexpr (refill && i == 3) read_b(std::integral_constant<int, j>{}, next, c0);
-      if constexpr (refill && j == 7) read_a(std::integral_constant<int, i>{}, next, c0);
+      if constexpr (refill && i == 3) read_b(std::integral_constant<int, j>{}, c0);
+      if constexpr (refill && j == 7) read_a(std::integral_constant<int, i>{}, c0);
       __builtin_amdgcn_sched_barrier(0);
     });
   };
   __builtin_amdgcn_sched_barrier(0);
-  step0(lds0);
+  step0();
   step1_row0_and_barrier();
   for (int kt = kt_lo; kt + 1 < kt_hi; ++kt) {
     const int stage = (kt - kt_lo) & 1;
-    const uint32_t next = lds0 + (stage ^ 1) * kStageBytes;
+    const uint32_t to_next = stage ? 0u - (uint32_t)kStageBytes : (uint32_t)kStageBytes;
     const KTile q2 = ktile(kt + 2);
-    step1_rest(c1, next, lds0 + stage * kStageBytes, q2);
-    step0(next);
+    step1_rest(c1, to_next, lds0 + stage * kStageBytes, q2);
+    step0();
     step1_row0_and_barrier();
   }
-  step1_rest(c0, lds0, lds0, KTile{});
+  step1_rest(c0, 0u, lds0, KTile{});
   }  // has_work
   // every piece (masked ones included) has landed and nobody reads the stages any more
   wait_loads_and_lds();
@@ -928,13 +949,13 @@ static int persistent_blocks(int max_tiles) {
   return want < cus ? want : cus;
 }
 
-template <int MODE>
-static int32_t launch_mfma(const GemmParams& p, int max_tiles, KernelId id, hipStream_t st) {
+template <int MODE, bool WHOLE_K>
+static int32_t launch_mfma_as(const GemmParams& p, int max_tiles, KernelId id, hipStream_t st) {
   static bool attr_set[kMaxDevices] = {};  // the LDS size is a per-device function attribute
   bool& done = attr_set[current_device()];
   if (!done) {
-    DYNMO_HIP_TRY(hipFuncSetAttribute((const void*)ffn_mfma_kernel<MODE>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      kLdsBytes + kTableBytes));
+    DYNMO_HIP_TRY(hipFuncSetAttribute((const void*)ffn_mfma_kernel<MODE, WHOLE_K>,
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes + kTableBytes));
     done = true;
   }
   if (max_tiles <= 0) return DYNMO_OK;
@@ -942,7 +963,7 @@ static int32_t launch_mfma(const GemmParams& p, int max_tiles, KernelId id, hipS
   const bool may_split = (MODE == MODE_DOWN || MODE == MODE_DOWN_FOLD || MODE == MODE_DX || MODE == MODE_DX_FOLD) && p.partial != nullptr;
   const int blocks = persistent_blocks(may_split ? kMaxPersistent : max_tiles);
   ProfScope prof(id, st);
-  ffn_mfma_kernel<MODE><<<dim3(blocks), dim3(kMfmaThreads), kLdsBytes + kTableBytes, st>>>(p);
+  ffn_mfma_kernel<MODE, WHOLE_K><<<dim3(blocks), dim3(kMfmaThreads), kLdsBytes + kTableBytes, st>>>(p);
   DYNMO_LAUNCH_CHECK();
   if (may_split) {
     ffn_split_reduce_kernel<<<dim3(kReduceParts * kMaxSplitTiles), dim3(256), 0, st>>>(p.partial, p.C0, p.ldc, p.N, p.scatter,
@@ -950,6 +971,15 @@ static int32_t launch_mfma(const GemmParams& p, int max_tiles, KernelId id, hipS
     DYNMO_LAUNCH_CHECK();
   }
   return DYNMO_OK;
+}
+
+template <int MODE>
+static int32_t launch_mfma(const GemmParams& p, int max_tiles, KernelId id, hipStream_t st) {
+  // MODE_DW contracts over an expert's rows, which both of its operands hold as [k][row] records
+  if constexpr (MODE != MODE_DW) {
+    if (p.K % BK == 0) return launch_mfma_as<MODE, true>(p, max_tiles, id, st);
+  }
+  return launch_mfma_as<MODE, false>(p, max_tiles, id, st);
 }
 
 bool ffn_mfma_supported(const dynmo_desc* d) {
