@@ -344,8 +344,8 @@ int32_t dynmo_profile_read(int32_t id, double* total_ms_host, int64_t* launches_
 /* Measurement aids, not part of the method: reference kernels whose duration the
  * caller times on `stream` to get the box's own ceilings next to the data-sheet ones.
  *
- * dynmo_peak_mfma_bf16: 256 workgroups of eight wavefronts issue `iters` x 8
- * v_mfma_f32_32x32x16_bf16 each on register operands; *flops_host (HOST) gets the
+ * dynmo_peak_mfma_bf16: 256 workgroups of eight wavefronts issue `iters` x 16
+ * v_mfma_f32_16x16x32_bf16 each on register operands; *flops_host (HOST) gets the
  * flop count of the launch.  operands: DEVICE, 8 KiB of bf16 data the operand
  * registers are filled from (random data draws the power of a real product), or
  * NULL for fixed small numbers.  sink: DEVICE, 256 * 512 floats, overwritten.

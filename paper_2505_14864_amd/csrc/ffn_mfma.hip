@@ -9,19 +9,21 @@
 //   DW      dW[e] = P_e^T Q_e over the rows of expert e (A, B both stored [K][M/N])
 //
 // Tiling: a 256x256 output tile per workgroup of eight wavefronts (4x2, 64x128
-// each, as 2x4 v_mfma_f32_32x32x16_bf16 blocks = 128 accumulator registers per
-// lane), K in steps of 64 through two LDS stages.  Two wavefronts share each SIMD:
-// one wavefront alone cannot issue MFMAs back to back (measured 87% of the MFMA
-// rate, against 99% with two).  Operand tiles go from global memory straight into
-// LDS (buffer loads with an LDS destination, 1 KB per wavefront instruction), one
-// such load per MFMA slot: no staging registers, no LDS store instructions, and no
-// burst of memory instructions that would hold up a wavefront's MFMAs.  The tiles
-// are unpadded and swizzled instead: the loads place each 16-byte piece where the
-// fragment reads are free of bank conflicts.  Tiles whose memory layout has K
-// contiguous are kept [row][k] in LDS; tiles whose memory layout has the row index
-// contiguous are kept [k][row] and read with ds_read_b64_tr_b16, which hands each
-// lane four consecutive k of one row -- so no operand is ever transposed in HBM or
-// by scalar LDS traffic.
+// each, as 4x8 v_mfma_f32_16x16x32_bf16 blocks = 128 accumulator registers per
+// lane), K in steps of 64 through two LDS stages.  The 16x16x32 instruction is used
+// because the part is power-limited under this load: with random operands and two
+// wavefronts per SIMD it sustains about a quarter more than 32x32x16 (measured: 80 %
+// against 55-65 % of the nominal rate in a register-only loop); one wavefront alone
+// issues it at only 60 %, so two share each SIMD.  Operand tiles go from global memory
+// straight into LDS (buffer loads with an LDS destination, 1 KB per wavefront
+// instruction), one such load every third MFMA slot: no staging registers, no LDS
+// store instructions, and no burst of memory instructions that would hold up a
+// wavefront's MFMAs.  The tiles are unpadded and swizzled instead: the loads place
+// each 16-byte piece where the fragment reads are free of bank conflicts.  Tiles whose
+// memory layout has K contiguous are kept [row][k] in LDS; tiles whose memory layout
+// has the row index contiguous are kept [k][row] and read with ds_read_b64_tr_b16,
+// which hands each lane four consecutive k of one row -- so no operand is ever
+// transposed in HBM or by scalar LDS traffic.
 //
 // Ragged rows: the row-tile list is derived on the device from seg_offsets, so
 // no host synchronisation is needed.  One persistent workgroup per compute unit

@@ -7,41 +7,45 @@
 namespace dynmo {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
-typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
-constexpr int kPeakBlocks = 256, kPeakThreads = 512, kPeakAcc = 8;
+constexpr int kPeakBlocks = 256, kPeakThreads = 512, kPeakAcc = 16;
 
-// Eight wavefronts per workgroup (two per SIMD), eight independent accumulator
-// blocks per wavefront: every MFMA has its operands in registers and depends only
-// on the MFMA issued eight instructions earlier.  The operands are either fixed
-// small numbers (few bits change between MFMAs: the least power the loop can draw)
-// or four A and four B fragments per lane taken from the caller's buffer (random
-// data makes the loop draw what a real product draws, and the clock follows).
+// Eight wavefronts per workgroup (two per SIMD), sixteen independent 16 x 16 accumulator
+// blocks per wavefront (two A fragments x eight B fragments, the instruction and the
+// operand reuse of the grouped GEMM's k loop): every MFMA has its operands in registers and
+// depends only on the MFMA issued sixteen instructions earlier.  The operands are either
+// fixed small numbers (few bits change between MFMAs: the least power the loop can draw) or
+// fragments taken from the caller's buffer (random data makes the loop draw what a real
+// product draws, and the clock follows).
 __global__ __launch_bounds__(kPeakThreads, 1) void peak_mfma_kernel(const u32x4* __restrict__ operands,
                                                                     float* __restrict__ sink, int iters) {
-  bf16x8_t a[4], b[4];
+  bf16x8_t a[2], b[8];
+  const int lane = threadIdx.x & 63;
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
+  for (int q = 0; q < 8; ++q) {
     if (operands) {
-      a[q] = __builtin_bit_cast(bf16x8_t, operands[q * 64 + (threadIdx.x & 63)]);
-      b[q] = __builtin_bit_cast(bf16x8_t, operands[(4 + q) * 64 + (threadIdx.x & 63)]);
+      // eight 1 KiB fragments in the buffer: 0, 1 feed A; 4..7, then 2, 3 and 4, 5 with the lanes rotated, feed B
+      if (q < 2) a[q] = __builtin_bit_cast(bf16x8_t, operands[q * 64 + lane]);
+      const int slot = q < 4 ? 4 + q : q - 2;
+      b[q] = __builtin_bit_cast(bf16x8_t, operands[slot * 64 + ((lane + (q >= 6 ? 32 : 0)) & 63)]);
     } else {
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        a[q][j] = (__bf16)(0.001f * (threadIdx.x & 63) + j);
+        if (q < 2) a[q][j] = (__bf16)(0.001f * lane + j);
         b[q][j] = (__bf16)(0.5f * j);
       }
     }
   }
-  f32x16_t acc[kPeakAcc];
+  f32x4_t acc[kPeakAcc];
 #pragma unroll
   for (int i = 0; i < kPeakAcc; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    for (int r = 0; r < 4; ++r) acc[i][r] = 0.f;
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
     for (int i = 0; i < kPeakAcc; ++i)
-      acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i & 3], b[(i >> 1) & 3], acc[i], 0, 0, 0);
+      acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i >> 3], b[i & 7], acc[i], 0, 0, 0);
   }
   float s = 0.f;
 #pragma unroll
@@ -70,8 +74,8 @@ extern "C" int32_t dynmo_peak_mfma_bf16(int32_t iters, const void* operands, flo
   peak_mfma_kernel<<<dim3(kPeakBlocks), dim3(kPeakThreads), 0, (hipStream_t)stream>>>((const u32x4*)operands, sink,
                                                                                       iters);
   DYNMO_LAUNCH_CHECK();
-  // one 32x32x16 MFMA = 2 * 32 * 32 * 16 flop per wavefront
-  *flops_host = (double)kPeakBlocks * (kPeakThreads / 64) * (double)iters * kPeakAcc * 32768.0;
+  // one 16x16x32 MFMA = 2 * 16 * 16 * 32 flop per wavefront
+  *flops_host = (double)kPeakBlocks * (kPeakThreads / 64) * (double)iters * kPeakAcc * 16384.0;
   return DYNMO_OK;
 }
 
