@@ -131,8 +131,8 @@ typedef uint32_t desc_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ desc_t make_desc(const bf16_t* p, uint32_t bytes) {
   const uint64_t a = (uint64_t)p;
   desc_t d;
-  d.x = (uint32_t)a;
-  d.y = (uint32_t)(a >> 32) & 0xffffu;
+  d.x = __builtin_amdgcn_readfirstlane((uint32_t)a);
+  d.y = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32) & 0xffffu);
   d.z = __builtin_amdgcn_readfirstlane(bytes);
   d.w = 0x00020000u;
   return d;
@@ -142,11 +142,13 @@ __device__ __forceinline__ desc_t make_desc(const bf16_t* p, uint32_t bytes) {
 // load (it would count it against its own waits) nor an LDS write (it would make every
 // transposed LDS read wait for all outstanding loads); the k loop waits for these loads
 // itself, once per k tile.  The memory clobber keeps LDS reads from moving across it.
-__device__ __forceinline__ void load_to_lds(desc_t d, uint32_t lds_offset, uint32_t global_offset) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+// The LDS destination is `lds_base` (wave-uniform, in a scalar register) + LDS_CONST.
+template <int LDS_CONST>
+__device__ __forceinline__ void load_to_lds(desc_t d, uint32_t lds_base, uint32_t global_offset) {
+  asm volatile("s_add_i32 m0, %0, %3\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                :
-               : "s"(lds_offset), "v"(global_offset), "s"(d)
-               : "memory");
+               : "s"(lds_base), "v"(global_offset), "s"(d), "n"(LDS_CONST)
+               : "memory", "scc");
 }
 
 // A prefetch into L2: four bytes per lane (one lane per 128-byte line) through the same path
@@ -321,13 +323,12 @@ __device__ __forceinline__ void read_frag(Frag<TRANS>& f, const FragAddr<TRANS, 
 }
 
 // Waits until at most N of this wavefront's LDS reads are outstanding (they complete in
-// order); `f` is the fragment the next MFMA is waiting for, named so that the MFMA cannot be
-// moved in front of the wait.
-template <int N, bool TRANS>
-__device__ __forceinline__ void wait_frag(Frag<TRANS>& f) {
+// order).  The callers fence it with __builtin_amdgcn_sched_barrier(0) so that the MFMAs that
+// need the data stay behind it.
+template <int N>
+__device__ __forceinline__ void wait_lds_but() {
   constexpr int n = N < 15 ? N : 15;
-  if constexpr (!TRANS) asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(f.v) : "n"(n));
-  else asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(f.lo), "+v"(f.hi) : "n"(n));
+  __builtin_amdgcn_s_waitcnt(0xc07f | (n << 8));  // lgkmcnt(n), no wait on the other counters
 }
 
 // ---- tile schedule ---------------------------------------------------------------
@@ -528,34 +529,78 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     r.kt_hi = parted_t ? (chunk_t + 1) * n_kt / split : n_kt;
     return r;
   };
-  auto ktile_of = [&](const Tile& tt, const KRange& r, int kt, bool second) {
-    int ph = IS_DX ? kt / r.kt_per_phase : 0;
-    if (IS_DX && ph > 1) ph = 1;
+  // The k tiles of an output tile are loaded strictly one after the other, so their
+  // descriptors come from an iterator that only adds strides (all of it scalar work: a
+  // from-scratch address computation per k tile sat in front of the k loop's MFMAs).
+  struct KIter {
+    const bf16_t* a;   // (row0, k) elements of the next k tile's operand tiles
+    const bf16_t* b;
+    int k_left;        // valid k from there to the end of the k range (of this phase)
+    int tiles_left;    // k tiles until this workgroup's share of the k range ends
+    int to_switch;     // MODE_DX: k tiles until the second phase starts
+    const bf16_t* a2;  // MODE_DX: where the second phase starts
+    const bf16_t* b2;
+  };
+  auto uniform_ptr = [](const bf16_t* q) {
+    const uint64_t v = (uint64_t)q;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (const bf16_t*)(((uint64_t)hi << 32) | lo);
+  };
+  // positioned at k tile kt of tile tt (`second`: operand B of the gate/up pairing comes from the second matrix)
+  auto kiter_at = [&](const Tile& tt, const KRange& r, int kt, bool second) {
+    const int ph = IS_DX && kt >= r.kt_per_phase ? 1 : 0;
     const int k0 = r.k_begin + (kt - ph * r.kt_per_phase) * BK;
+    auto addr_a = [&](int phase, int k) {
+      const bf16_t* A = phase == 0 ? p.A1 : p.A2;
+      return uniform_ptr(A_TRANS ? A + (long)k * p.lda + tt.m0 : A + (gathered ? 0 : (long)tt.m0 * p.lda) + k);
+    };
+    auto addr_b = [&](int phase, int k) {
+      const bf16_t* B = ((phase == 1 || second) ? p.B2 : p.B1) + (MODE == MODE_DW ? 0 : (long)tt.e * p.b_expert_stride);
+      return uniform_ptr(B_TRANS ? B + (long)k * p.ldb + tt.n0 : B + (long)tt.n0 * p.ldb + k);
+    };
+    KIter it;
+    it.a = addr_a(ph, k0);
+    it.b = addr_b(ph, k0);
+    it.k_left = __builtin_amdgcn_readfirstlane(r.k_end - k0);
+    it.tiles_left = __builtin_amdgcn_readfirstlane(r.kt_hi - kt);
+    it.to_switch = IS_DX && ph == 0 ? __builtin_amdgcn_readfirstlane(r.kt_per_phase - kt) : 0x40000000;
+    it.a2 = IS_DX ? addr_a(1, 0) : nullptr;
+    it.b2 = IS_DX ? addr_b(1, 0) : nullptr;
+    return it;
+  };
+  // the descriptors of the k tile the iterator stands at; moves it on to the next one
+  auto knext = [&](KIter& it) {
     KTile q;
-    q.k_left = kt < r.kt_hi ? r.k_end - k0 : 0;
-    const bf16_t* A = ph == 0 ? p.A1 : p.A2;
-    const bf16_t* Bw = ((IS_DX && ph == 1) || second) ? p.B2 : p.B1;
-    const bf16_t* B = Bw + (MODE == MODE_DW ? 0 : (long)tt.e * p.b_expert_stride);
+    q.k_left = it.tiles_left > 0 ? it.k_left : 0;
     // record counts: nothing past the k range is fetched (zeros land in LDS instead); a [k][row]
     // operand's k-rows are whole records, so its count is also the k mask of a ragged last tile
-    // (k_left is the same in every lane, which the compiler cannot see: it comes out of the LDS table)
-    const int k_left_u = __builtin_amdgcn_readfirstlane(q.k_left);
-    const uint32_t k_rows = (uint32_t)max(0, min(k_left_u, BK));
-    const uint32_t any = k_left_u > 0 ? 0x7ffffffeu : 0u;
-    q.a = make_desc(A_TRANS ? A + (long)k0 * p.lda + tt.m0 : A + (gathered ? 0 : (long)tt.m0 * p.lda) + k0,
-                    A_TRANS ? k_rows * lda_b : any);
-    q.b = make_desc(B_TRANS ? B + (long)k0 * p.ldb + tt.n0 : B + (long)tt.n0 * p.ldb + k0, B_TRANS ? k_rows * ldb_b : any);
+    const uint32_t k_rows = (uint32_t)max(0, min(q.k_left, BK));
+    const uint32_t any = q.k_left > 0 ? 0x7ffffffeu : 0u;
+    q.a = make_desc(it.a, A_TRANS ? k_rows * lda_b : any);
+    q.b = make_desc(it.b, B_TRANS ? k_rows * ldb_b : any);
+    it.a += A_TRANS ? (long)BK * p.lda : BK;
+    it.b += B_TRANS ? (long)BK * p.ldb : BK;
+    it.k_left -= BK;
+    it.tiles_left -= 1;
+    if (IS_DX) {
+      it.to_switch -= 1;
+      if (it.to_switch == 0) {
+        it.a = it.a2;
+        it.b = it.b2;
+        it.k_left = p.K;
+      }
+    }
     return q;
   };
   // this wavefront's pieces of k tile q (pieces pa / pb) into the stage at LDS offset `stage`
-  auto dma_a = [&](const Pieces& pa, const KTile& q, uint32_t stage, int j) {
-    load_to_lds(q.a, stage + (wave_u * kPieces + j) * 1024,
-                A_TRANS || WHOLE_K || pa.kpos[j] < q.k_left ? pa.off[j] : kOob);
+  const uint32_t wave_pieces = wave_u * kPieces * 1024;  // this wavefront's pieces inside an operand tile
+  auto dma_a = [&](const Pieces& pa, const KTile& q, uint32_t stage, auto J) {
+    constexpr int j = decltype(J)::value;
+    load_to_lds<j * 1024>(q.a, stage + wave_pieces, A_TRANS || WHOLE_K || pa.kpos[j] < q.k_left ? pa.off[j] : kOob);
   };
-  auto dma_b = [&](const Pieces& pb, const KTile& q, uint32_t stage, int j) {
-    load_to_lds(q.b, stage + kTileBytes + (wave_u * kPieces + j) * 1024,
-                B_TRANS || WHOLE_K || pb.kpos[j] < q.k_left ? pb.off[j] : kOob);
+  auto dma_b = [&](const Pieces& pb, const KTile& q, uint32_t stage, auto J) {
+    constexpr int j = decltype(J)::value;
+    load_to_lds<kTileBytes + j * 1024>(q.b, stage + wave_pieces, B_TRANS || WHOLE_K || pb.kpos[j] < q.k_left ? pb.off[j] : kOob);
   };
   // L2 prefetch.  The workgroups of an XCD that run side by side share operand tiles (a 4 x 8
   // patch of output tiles: 8 share each A tile, 4 each B tile) and ask for the same lines at
@@ -662,9 +707,9 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   // first 16-row block of this wavefront in each operand tile (gate/up: 64 gate rows, and the 64 matching up rows 128 further on)
   FragAddr<A_TRANS, 4> fra = frag_addr<A_TRANS, 4>(lds0, (wave_u >> 1) * 4);
   FragAddr<B_TRANS, 8> frb = frag_addr<B_TRANS, 8>(lds0, MODE == MODE_GATEUP ? (wave_u & 1) * 4 : (wave_u & 1) * 8);
-  auto ktile = [&](int kt) { return ktile_of(t, kr, kt, second_b); };
+  KIter kit = kiter_at(t, kr, kt_lo, second_b);  // the k tiles to load, in order
   const Touch th = touch_of(t);
-  auto ktile_touched = [&](int kt) { return ktile_of(t, kr, kt, th.second); };
+  KIter kit_touch = kiter_at(t, kr, kt_lo + 2, th.second);  // the k tiles to prefetch, in order
   // A fragment of row block I / B fragment of column block J for k step H
   // (the stage read is the one fra / frb point into)
   auto read_a = [&](auto I, auto H) {
@@ -683,17 +728,19 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   const std::integral_constant<int, 1> c1;
   const std::integral_constant<int, 3> c3;
 
-  if (!first_in_flight) {
-    const KTile q0 = ktile(kt_lo);
-    static_for<kPieces>([&](auto J) { dma_a(pa, q0, lds0, J); });
-    static_for<kPieces>([&](auto J) { dma_b(pb, q0, lds0, J); });
+  {
+    const KTile q0 = knext(kit);
+    if (!first_in_flight) {
+      static_for<kPieces>([&](auto J) { dma_a(pa, q0, lds0, J); });
+      static_for<kPieces>([&](auto J) { dma_b(pb, q0, lds0, J); });
+    }
   }
   {
-    const KTile q1 = ktile(kt_lo + 1);
+    const KTile q1 = knext(kit);
     static_for<kPieces>([&](auto J) { dma_a(pa, q1, lds0 + kStageBytes, J); });
     static_for<kPieces>([&](auto J) { dma_b(pb, q1, lds0 + kStageBytes, J); });
   }
-  touch(ktile_touched(kt_lo + 2), th);
+  if constexpr (TOUCHES) touch(knext(kit_touch), th);
   wait_loads_but<2 * kPieces + (TOUCHES ? 1 : 0)>();  // the first tile has landed
   wg_barrier();
   // A wavefront whose 64 x 128 part lies wholly outside the valid rows or columns (the
@@ -707,10 +754,10 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
       wait_pieces();
       wg_barrier();
       const uint32_t freed = lds0 + ((kt - kt_lo) & 1) * kStageBytes;
-      const KTile q2 = ktile(kt + 2);
+      const KTile q2 = knext(kit);
       static_for<kPieces>([&](auto J) { dma_a(pa, q2, freed, J); });
       static_for<kPieces>([&](auto J) { dma_b(pb, q2, freed, J); });
-      touch(ktile_touched(kt + 3), th);
+      if constexpr (TOUCHES) touch(knext(kit_touch), th);
     }
   } else if (kt_lo < kt_hi) {  // (an expert without rows has nothing to contract: its tiles of MODE_DW stay zero)
   // Order of a step's fragment reads: A 0, 1, 2 (each after its row), B 0 .. 7 (row 3), A 3.
@@ -720,9 +767,14 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   static_for<8>([&](auto J) { read_b(J, c0); });
   read_a(c3, c0);
   // row 0 of a step: every MFMA waits for its B fragment
+  // (three waits: for B 0..3, then B 4, 5, then B 6, 7)
   auto row0 = [&]() {
     static_for<8>([&](auto J) {
-      wait_frag<(7 - decltype(J)::value) * RB + RA>(fb[decltype(J)::value]);
+      constexpr int j = decltype(J)::value;
+      if constexpr (j == 0 || j == 4 || j == 6) {
+        wait_lds_but<(7 - (j == 0 ? 3 : j + 1)) * RB + RA>();
+        __builtin_amdgcn_sched_barrier(0);
+      }
       mfma(c0, J);
       __builtin_amdgcn_sched_barrier(0);
     });
@@ -734,7 +786,10 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     __builtin_amdgcn_sched_barrier(0);
     static_for<24>([&](auto M) {
       constexpr int m = decltype(M)::value, i = 1 + (m >> 3), j = m & 7;
-      if constexpr (m == 16) wait_frag<3 * RA>(fa[3]);  // A 3 of this step is followed by A 0, 1, 2 of the next
+      if constexpr (m == 16) {  // A 3 of this step is followed by A 0, 1, 2 of the next
+        wait_lds_but<3 * RA>();
+        __builtin_amdgcn_sched_barrier(0);
+      }
       mfma(std::integral_constant<int, i>{}, std::integral_constant<int, j>{});
       if constexpr (i == 3) read_b(std::integral_constant<int, j>{}, c1);
       if constexpr (j == 7) read_a(std::integral_constant<int, i>{}, c1);
@@ -760,8 +815,8 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
       constexpr int m = decltype(M)::value, i = 1 + (m >> 3), j = m & 7;
       if constexpr (refill && m % 3 == 0) {
         constexpr int piece = m / 3;
-        if constexpr (piece < kPieces) dma_a(pa, q2, freed, piece);
-        else dma_b(pb, q2, freed, piece - kPieces);
+        if constexpr (piece < kPieces) dma_a(pa, q2, freed, std::integral_constant<int, piece>{});
+        else dma_b(pb, q2, freed, std::integral_constant<int, piece - kPieces>{});
       }
       mfma(std::integral_constant<int, i>{}, std::integral_constant<int, j>{});
       if constexpr (refill && i == 3) read_b(std::integral_constant<int, j>{}, c0);
@@ -776,8 +831,10 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   for (int kt = kt_lo; kt + 1 < kt_hi; ++kt) {
     const int stage = (kt - kt_lo) & 1;
     const uint32_t to_next = stage ? 0u - (uint32_t)kStageBytes : (uint32_t)kStageBytes;
-    const KTile q2 = ktile(kt + 2);
-    step1_rest(c1, to_next, lds0 + stage * kStageBytes, q2, ktile_touched(kt + 3));
+    const KTile q2 = knext(kit);
+    KTile q3{};
+    if constexpr (TOUCHES) q3 = knext(kit_touch);
+    step1_rest(c1, to_next, lds0 + stage * kStageBytes, q2, q3);
     step0();
     step1_row0_and_barrier();
   }
@@ -793,7 +850,8 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     const Tile tn = tile_at(round + 1);
     const KRange rn = krange(tn, CAN_SPLIT && round + 1 == my_rounds);
     const Pieces pan = pieces_a(tn), pbn = pieces_b(tn);
-    const KTile qn = ktile_of(tn, rn, rn.kt_lo, second_b);
+    KIter kn = kiter_at(tn, rn, rn.kt_lo, second_b);
+    const KTile qn = knext(kn);
     static_for<kPieces>([&](auto J) { dma_a(pan, qn, lds0, J); });
     static_for<kPieces>([&](auto J) { dma_b(pbn, qn, lds0, J); });
   }
