@@ -253,7 +253,8 @@ __device__ __forceinline__ Pieces pieces_rowk_gather(uint32_t ld_bytes, int row0
 // reached by a compile-time constant.  [row][k] tiles: one address per 32-wide k step (the
 // swizzle mixes the k piece into the address; the 16-row block adds block * 2048).
 // [k][row] tiles: one address per 16-row block (the swizzle mixes the block into the address;
-// the k step adds step * 32 * 512).  `first16` is the wavefront's first 16-row block; it is even.
+// the k step adds step * 32 * 512).  `first16` is the wavefront's first 16-row block, its n-th
+// block lies STRIDE blocks further on each time.
 // The k loop moves the addresses from stage to stage in place (shift()).
 template <bool TRANS, int BLOCKS>
 struct FragAddr {
@@ -265,7 +266,7 @@ struct FragAddr {
   }
 };
 
-template <bool TRANS, int BLOCKS>
+template <bool TRANS, int BLOCKS, int STRIDE>
 __device__ __forceinline__ FragAddr<TRANS, BLOCKS> frag_addr(uint32_t stage, int first16) {
   FragAddr<TRANS, BLOCKS> fa;
   const int lane = tid_now() & 63;
@@ -280,7 +281,7 @@ __device__ __forceinline__ FragAddr<TRANS, BLOCKS> frag_addr(uint32_t stage, int
     const int k = g * 8 + (s >> 2);
 #pragma unroll
     for (int n = 0; n < BLOCKS; ++n) {
-      const int blk = (first16 + n) >> 1, half = (first16 + n) & 1;
+      const int blk = (first16 + n * STRIDE) >> 1, half = (first16 + n * STRIDE) & 1;
       const int stored = (blk & 4) | ((blk ^ k) & 3);
       fa.a[n] = stage + (uint32_t)(k * 512 + stored * 64 + (((g & 1) ^ half) << 5) + (s & 3) * 8);
     }
@@ -306,19 +307,19 @@ struct Frag<true> {
 template <bool TRANS>
 constexpr int kReadsPerFrag = TRANS ? 2 : 1;
 
-// Reads the fragment of the wavefront's 16-row block N16 (relative to its first one) for the
-// 32-wide k step H into `f`; TILE_OFF = the operand tile's offset inside a stage.  Written
+// Reads the wavefront's IDX-th fragment, which lies ROW16 16-row blocks behind its first one, for
+// the 32-wide k step H into `f`; TILE_OFF = the operand tile's offset inside a stage.  Written
 // as assembly with the fragment as an in-out operand: the new value then takes the registers
 // of the old one (left to itself the compiler gives every read of the unrolled k tile fresh
 // registers, twice the fragments' share of the file, and spills loop invariants instead).
 // The compiler therefore does not know these reads; wait_frag() below stands in for its waits.
-template <bool TRANS, int N16, int H, int TILE_OFF, int BLOCKS>
+template <bool TRANS, int IDX, int ROW16, int H, int TILE_OFF, int BLOCKS>
 __device__ __forceinline__ void read_frag(Frag<TRANS>& f, const FragAddr<TRANS, BLOCKS>& fa) {
   if constexpr (!TRANS) {
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "+v"(f.v) : "v"(fa.a[H]), "n"(TILE_OFF + N16 * 2048) : "memory");
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "+v"(f.v) : "v"(fa.a[H]), "n"(TILE_OFF + ROW16 * 2048) : "memory");
   } else {
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "+v"(f.lo) : "v"(fa.a[N16]), "n"(TILE_OFF + H * 32 * 512) : "memory");
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "+v"(f.hi) : "v"(fa.a[N16]), "n"(TILE_OFF + H * 32 * 512 + 4 * 512) : "memory");
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "+v"(f.lo) : "v"(fa.a[IDX]), "n"(TILE_OFF + H * 32 * 512) : "memory");
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "+v"(f.hi) : "v"(fa.a[IDX]), "n"(TILE_OFF + H * 32 * 512 + 4 * 512) : "memory");
   }
 }
 
@@ -485,7 +486,14 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     first = min(xcd * per, all - tail_tiles);
     mine = min(per, all - tail_tiles - first);
   }
-  const int my_rounds = slot < mine ? (mine - slot + slots - 1) / slots : 0;
+  // In round r the XCD's workgroups take its tiles r * slots .. + slots - 1, workgroup `slot` the one at
+  // (slot + 5 r) mod slots of them.  The rotation changes nothing about which tiles run side by side; it
+  // spreads the cheap ragged row tiles, which recur at a fixed place of that window when an expert has a
+  // multiple of four row tiles (a multiple of eight places otherwise: hence a step that is not), over the
+  // workgroups, whose tile counts are fixed.
+  auto place = [&](int round) { return (slot + 5 * round) % slots; };
+  const int whole_rounds = mine / slots;
+  const int my_rounds = whole_rounds + (place(whole_rounds) < mine - whole_rounds * slots ? 1 : 0);
   const int tail_tile = (xcd / split) * slots + slot;  // index among the split tiles
   const bool has_part = split > 1 && tail_tile < tail_tiles;
   if (CAN_SPLIT && p.partial != nullptr && blockIdx.x == 0 && threadIdx.x == 0) {
@@ -656,7 +664,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   const int n_rounds = my_rounds + (has_part ? 1 : 0);
   auto tile_at = [&](int round) {
     const bool parted_t = CAN_SPLIT && round == my_rounds;
-    return decode_tile(table, tb, parted_t ? tb.total - tail_tiles + tail_tile : first + round * slots + slot,
+    return decode_tile(table, tb, parted_t ? tb.total - tail_tiles + tail_tile : first + round * slots + place(round),
                        MODE == MODE_DW, p.M, TILE_N);
   };
   bool first_in_flight = false;  // the first k tile of the tile about to start is already on its way to stage 0
@@ -670,7 +678,12 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm = wave >> 1, wn = wave & 1;  // 4 x 2 wavefronts, 64 x 128 outputs each
 
-  f32x4_t acc[4][8];  // 16 x 16 blocks: block (i, j) = rows 16 i .., columns 16 j .. of the wavefront's part
+  // 16 x 16 blocks.  The wavefront's part is NOT a contiguous 64 rows: its row block i is the
+  // tile's 16-row block 4 i + wm, so that in a ragged row tile (the valid rows are a prefix) every
+  // wavefront keeps a share of the valid blocks -- ceil(valid blocks / 4) each -- instead of the
+  // first one or two wavefronts of each column half doing all the work alone on their SIMDs.
+  // Block (i, j) = rows 16 (4 i + wm) .., columns 16 j .. (+ 128 wn) of the tile.
+  f32x4_t acc[4][8];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -705,20 +718,20 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   constexpr int RA = kReadsPerFrag<A_TRANS>, RB = kReadsPerFrag<B_TRANS>;
   const Pieces pa = pieces_a(t), pb = pieces_b(t);
   // first 16-row block of this wavefront in each operand tile (gate/up: 64 gate rows, and the 64 matching up rows 128 further on)
-  FragAddr<A_TRANS, 4> fra = frag_addr<A_TRANS, 4>(lds0, (wave_u >> 1) * 4);
-  FragAddr<B_TRANS, 8> frb = frag_addr<B_TRANS, 8>(lds0, MODE == MODE_GATEUP ? (wave_u & 1) * 4 : (wave_u & 1) * 8);
+  FragAddr<A_TRANS, 4> fra = frag_addr<A_TRANS, 4, 4>(lds0, wave_u >> 1);
+  FragAddr<B_TRANS, 8> frb = frag_addr<B_TRANS, 8, 1>(lds0, MODE == MODE_GATEUP ? (wave_u & 1) * 4 : (wave_u & 1) * 8);
   KIter kit = kiter_at(t, kr, kt_lo, second_b);  // the k tiles to load, in order
   const Touch th = touch_of(t);
   KIter kit_touch = kiter_at(t, kr, kt_lo + 2, th.second);  // the k tiles to prefetch, in order
   // A fragment of row block I / B fragment of column block J for k step H
   // (the stage read is the one fra / frb point into)
   auto read_a = [&](auto I, auto H) {
-    read_frag<A_TRANS, decltype(I)::value, decltype(H)::value, 0>(fa[decltype(I)::value], fra);
+    read_frag<A_TRANS, decltype(I)::value, 4 * decltype(I)::value, decltype(H)::value, 0>(fa[decltype(I)::value], fra);
   };
   auto read_b = [&](auto J, auto H) {
     constexpr int j = decltype(J)::value;
     constexpr int n16 = MODE == MODE_GATEUP ? (j & 3) + (j >> 2) * 8 : j;
-    read_frag<B_TRANS, n16, decltype(H)::value, kTileBytes>(fb[j], frb);
+    read_frag<B_TRANS, j, n16, decltype(H)::value, kTileBytes>(fb[j], frb);
   };
   auto mfma = [&](auto I, auto J) {
     constexpr int i = decltype(I)::value, j = decltype(J)::value;
@@ -726,7 +739,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   };
   const std::integral_constant<int, 0> c0;
   const std::integral_constant<int, 1> c1;
-  const std::integral_constant<int, 3> c3;
+  const std::integral_constant<int, 2> c2_;
 
   {
     const KTile q0 = knext(kit);
@@ -743,13 +756,105 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   if constexpr (TOUCHES) touch(knext(kit_touch), th);
   wait_loads_but<2 * kPieces + (TOUCHES ? 1 : 0)>();  // the first tile has landed
   wg_barrier();
-  // A wavefront whose 64 x 128 part lies wholly outside the valid rows or columns (the
-  // ragged last row tile of an expert, a narrow last column tile) only keeps up the
-  // staging: it moves its pieces and meets the barriers, but reads no fragments and
-  // issues no MFMAs, which leaves the SIMD and the LDS to the wavefronts that have work.
-  const bool has_work = t.m0 + (wave_u >> 1) * 64 < t.m_end &&
-                        (MODE == MODE_GATEUP ? t.n0 + (wave_u & 1) * 64 : t.n0 + (wave_u & 1) * 128) < n_end;
-  if (!has_work) {
+  const int valid16 = min(16, (t.m_end - t.m0 + 15) / 16);  // valid 16-row blocks of the tile (a prefix)
+  const bool cols_ok = (MODE == MODE_GATEUP ? t.n0 + (wave_u & 1) * 64 : t.n0 + (wave_u & 1) * 128) < n_end;
+  // row blocks this wavefront has work in: blocks wm, wm + 4, .. below valid16
+  const int my_rows = __builtin_amdgcn_readfirstlane(cols_ok && valid16 > (wave_u >> 1) ? (valid16 - (wave_u >> 1) + 3) / 4 : 0);
+  // The k loop of a wavefront with ROWS row blocks of work (1..4; 4 = the full part).
+  // Order of a step's fragment reads: A 0 .. ROWS-2 (each after its row), B 0 .. 7 (in the last
+  // row, each after its last MFMA), A ROWS-1.  Reads complete in order, so what a MFMA has to
+  // wait for is the number of reads issued after its youngest fragment.
+  auto work = [&](auto ROWS_C) {
+    constexpr int ROWS = decltype(ROWS_C)::value, LAST = ROWS - 1;
+    const std::integral_constant<int, LAST> c_last;
+    static_for<LAST>([&](auto I) { read_a(I, c0); });
+    static_for<8>([&](auto J) { read_b(J, c0); });
+    read_a(c_last, c0);
+    // all MFMAs of one k step; WHAT = 0: first step of a k tile (fragments of step 1 follow as registers fall
+    // free), 1: row 0 of step 1 only, 2: rows 1.. of step 1 with the refill, 3: rows 1.. of step 1 without
+    auto mfmas = [&](auto WHAT_C, uint32_t freed, const KTile& q2, const KTile& q3) {
+      constexpr int WHAT = decltype(WHAT_C)::value;
+      constexpr int FIRST_SLOT = WHAT >= 2 ? 8 : 0, END_SLOT = WHAT == 1 ? 8 : 8 * ROWS;
+      constexpr int REFILL_SLOTS = 8 * ROWS - 8;  // MFMA slots behind the barrier (none if ROWS == 1)
+      static_for<END_SLOT - FIRST_SLOT>([&](auto M) {
+        constexpr int m = decltype(M)::value + FIRST_SLOT, i = m >> 3, j = m & 7;
+        if constexpr (WHAT <= 1 && i == 0) {
+          // row 0: B 0..3, then B 4, 5, then B 6, 7 (B j is followed by B j+1 .. 7 and A LAST); with one row
+          // block, A LAST is A 0 itself, the youngest read of all
+          if constexpr (ROWS == 1 && j == 0) {
+            wait_lds_but<0>();
+            __builtin_amdgcn_sched_barrier(0);
+          } else if constexpr (ROWS > 1 && (j == 0 || j == 4 || j == 6)) {
+            wait_lds_but<(7 - (j == 0 ? 3 : j + 1)) * RB + RA>();
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+        if constexpr (WHAT != 1 && ROWS > 1 && m == 8 * LAST) {  // A LAST of this step is followed by A 0 .. LAST-1 of the next
+          wait_lds_but<LAST * RA>();
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (WHAT == 2) {
+          // one piece of the refill every REFILL_SLOTS / 8 slots, the L2 prefetch in the last slot
+          constexpr int every = REFILL_SLOTS / 8, s = m - 8;
+          if constexpr (s % every == 0) {
+            constexpr int piece = s / every;
+            if constexpr (piece < kPieces) dma_a(pa, q2, freed, std::integral_constant<int, piece>{});
+            else dma_b(pb, q2, freed, std::integral_constant<int, piece - kPieces>{});
+          }
+        }
+        mfma(std::integral_constant<int, i>{}, std::integral_constant<int, j>{});
+        if constexpr (WHAT == 0 || WHAT == 2) {
+          constexpr auto H = std::integral_constant<int, WHAT == 0 ? 1 : 0>{};
+          if constexpr (i == LAST) read_b(std::integral_constant<int, j>{}, H);
+          if constexpr (j == 7) read_a(std::integral_constant<int, i>{}, H);
+        }
+        if constexpr (WHAT == 2 && m == 8 * ROWS - 1) touch(q3, th);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    };
+    const std::integral_constant<int, 2> c2;
+    auto step0 = [&]() { mfmas(c0, 0u, KTile{}, KTile{}); };
+    auto step1_row0_and_barrier = [&]() {
+      mfmas(c1, 0u, KTile{}, KTile{});
+      wait_pieces();
+      wg_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    // behind the barrier: fra / frb move on to the next tile's stage; its first fragments and the refill of the
+    // stage just freed go between the remaining MFMAs of step 1 (all at once if there are none)
+    auto step1_rest = [&](uint32_t to_next, uint32_t freed, const KTile& q2, const KTile& q3) {
+      fra.shift(to_next);
+      frb.shift(to_next);
+      if constexpr (ROWS == 1) {
+        static_for<kPieces>([&](auto J) { dma_a(pa, q2, freed, J); });
+        static_for<kPieces>([&](auto J) { dma_b(pb, q2, freed, J); });
+        touch(q3, th);
+        static_for<8>([&](auto J) { read_b(J, c0); });
+        read_a(c0, c0);
+        __builtin_amdgcn_sched_barrier(0);
+      } else {
+        if constexpr (LAST > 0) read_a(c0, c0);
+        mfmas(c2, freed, q2, q3);
+      }
+    };
+    __builtin_amdgcn_sched_barrier(0);
+    step0();
+    step1_row0_and_barrier();
+    for (int kt = kt_lo; kt + 1 < kt_hi; ++kt) {
+      const int stage = (kt - kt_lo) & 1;
+      const uint32_t to_next = stage ? 0u - (uint32_t)kStageBytes : (uint32_t)kStageBytes;
+      const KTile q2 = knext(kit);
+      KTile q3{};
+      if constexpr (TOUCHES) q3 = knext(kit_touch);
+      step1_rest(to_next, lds0 + stage * kStageBytes, q2, q3);
+      step0();
+      step1_row0_and_barrier();
+    }
+    if constexpr (ROWS > 1) mfmas(std::integral_constant<int, 3>{}, 0u, KTile{}, KTile{});
+  };
+  if (my_rows == 0) {
+    // No valid rows or columns in this wavefront's part: it only keeps up the staging -- moves its
+    // pieces and meets the barriers -- and leaves the SIMD and the LDS to the others.
     for (int kt = kt_lo; kt < kt_hi; ++kt) {
       wait_pieces();
       wg_barrier();
@@ -760,86 +865,11 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
       if constexpr (TOUCHES) touch(knext(kit_touch), th);
     }
   } else if (kt_lo < kt_hi) {  // (an expert without rows has nothing to contract: its tiles of MODE_DW stay zero)
-  // Order of a step's fragment reads: A 0, 1, 2 (each after its row), B 0 .. 7 (row 3), A 3.
-  // Reads complete in order, so what a MFMA has to wait for is the number of reads issued
-  // after its youngest fragment: B j of the step before is followed by B j+1 .. 7 and A 3.
-  static_for<3>([&](auto I) { read_a(I, c0); });
-  static_for<8>([&](auto J) { read_b(J, c0); });
-  read_a(c3, c0);
-  // row 0 of a step: every MFMA waits for its B fragment
-  // (three waits: for B 0..3, then B 4, 5, then B 6, 7)
-  auto row0 = [&]() {
-    static_for<8>([&](auto J) {
-      constexpr int j = decltype(J)::value;
-      if constexpr (j == 0 || j == 4 || j == 6) {
-        wait_lds_but<(7 - (j == 0 ? 3 : j + 1)) * RB + RA>();
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      mfma(c0, J);
-      __builtin_amdgcn_sched_barrier(0);
-    });
-  };
-  // The loop is rotated so that its body starts right behind the barrier.
-  auto step0 = [&]() {
-    row0();
-    read_a(c0, c1);
-    __builtin_amdgcn_sched_barrier(0);
-    static_for<24>([&](auto M) {
-      constexpr int m = decltype(M)::value, i = 1 + (m >> 3), j = m & 7;
-      if constexpr (m == 16) {  // A 3 of this step is followed by A 0, 1, 2 of the next
-        wait_lds_but<3 * RA>();
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      mfma(std::integral_constant<int, i>{}, std::integral_constant<int, j>{});
-      if constexpr (i == 3) read_b(std::integral_constant<int, j>{}, c1);
-      if constexpr (j == 7) read_a(std::integral_constant<int, i>{}, c1);
-      __builtin_amdgcn_sched_barrier(0);
-    });
-  };
-  auto step1_row0_and_barrier = [&]() {
-    row0();
-    wait_pieces();
-    wg_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-  };
-  // Rows 1..3 of step 1.  REFILL: with the next tile's first fragments (fra / frb move on to its
-  // stage) and the refill of the stage just freed.
-  auto step1_rest = [&](auto REFILL, uint32_t to_next, uint32_t freed, const KTile& q2, const KTile& q3) {
-    constexpr bool refill = decltype(REFILL)::value != 0;
-    if constexpr (refill) {
-      fra.shift(to_next);
-      frb.shift(to_next);
-      read_a(c0, c0);
-    }
-    static_for<24>([&](auto M) {
-      constexpr int m = decltype(M)::value, i = 1 + (m >> 3), j = m & 7;
-      if constexpr (refill && m % 3 == 0) {
-        constexpr int piece = m / 3;
-        if constexpr (piece < kPieces) dma_a(pa, q2, freed, std::integral_constant<int, piece>{});
-        else dma_b(pb, q2, freed, std::integral_constant<int, piece - kPieces>{});
-      }
-      mfma(std::integral_constant<int, i>{}, std::integral_constant<int, j>{});
-      if constexpr (refill && i == 3) read_b(std::integral_constant<int, j>{}, c0);
-      if constexpr (refill && j == 7) read_a(std::integral_constant<int, i>{}, c0);
-      if constexpr (refill && m == 23) touch(q3, th);
-      __builtin_amdgcn_sched_barrier(0);
-    });
-  };
-  __builtin_amdgcn_sched_barrier(0);
-  step0();
-  step1_row0_and_barrier();
-  for (int kt = kt_lo; kt + 1 < kt_hi; ++kt) {
-    const int stage = (kt - kt_lo) & 1;
-    const uint32_t to_next = stage ? 0u - (uint32_t)kStageBytes : (uint32_t)kStageBytes;
-    const KTile q2 = knext(kit);
-    KTile q3{};
-    if constexpr (TOUCHES) q3 = knext(kit_touch);
-    step1_rest(c1, to_next, lds0 + stage * kStageBytes, q2, q3);
-    step0();
-    step1_row0_and_barrier();
+    if (my_rows == 4) work(std::integral_constant<int, 4>{});
+    else if (my_rows == 3) work(std::integral_constant<int, 3>{});
+    else if (my_rows == 2) work(c2_);
+    else work(c1);
   }
-  step1_rest(c0, 0u, lds0, KTile{}, KTile{});
-  }  // has_work
   // every piece (masked ones included) has landed and nobody reads the stages any more
   wait_loads_and_lds();
   wg_barrier();
@@ -856,10 +886,10 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     static_for<kPieces>([&](auto J) { dma_b(pbn, qn, lds0, J); });
   }
 
-  // ---- epilogue.  Accumulator element r of block (i, j) is row 16 i + (lane/16)*4 + r,
-  // column 16 j + lane%16 of the wavefront's 64x128 part.  Each wavefront passes sixteen
-  // rows at a time (the eight blocks of row block i) through its own LDS patch (fp32, padded
-  // rows) so that global memory sees 16-byte accesses along rows.  The patch belongs to the wavefront alone and a
+  // ---- epilogue.  Accumulator element r of block (i, j) is row 16 (4 i + wm) + (lane/16)*4 + r,
+  // column 128 wn + 16 j + lane%16 of the tile.  Each wavefront passes sixteen rows at a
+  // time (the eight blocks of row block i; only the row blocks it has work in) through its own
+  // LDS patch (fp32, padded rows) so that global memory sees 16-byte accesses along rows.  The patch belongs to the wavefront alone and a
   // wavefront's LDS accesses complete in order, so neither reusing the patch nor reading it
   // back needs a workgroup barrier.
   // The lane and wavefront indices are taken afresh behind a compiler barrier: the addresses
@@ -886,7 +916,8 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   constexpr int kPasses = kEpRows / 4;  // 64 lanes cover 4 rows x 128 columns (gate/up: 8 rows x 64 + 64) per pass
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int tile_row = wm * 64 + i * kEpRows;  // first of the sixteen rows, inside the tile
+    if (i >= my_rows) break;
+    const int tile_row = (i * 4 + wm) * kEpRows;  // first of the sixteen rows, inside the tile
     const int band_row = t.m0 + tile_row;
     // folded combine / scatter: the rows' token indices, then (once their accumulators have
     // left the registers) weights and residual rows, are requested all at once, so that their
