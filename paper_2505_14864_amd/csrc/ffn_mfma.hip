@@ -312,7 +312,7 @@ constexpr int kReadsPerFrag = TRANS ? 2 : 1;
 // as assembly with the fragment as an in-out operand: the new value then takes the registers
 // of the old one (left to itself the compiler gives every read of the unrolled k tile fresh
 // registers, twice the fragments' share of the file, and spills loop invariants instead).
-// The compiler therefore does not know these reads; wait_frag() below stands in for its waits.
+// The compiler therefore does not know these reads; wait_lds_but() below stands in for its waits.
 template <bool TRANS, int IDX, int ROW16, int H, int TILE_OFF, int BLOCKS>
 __device__ __forceinline__ void read_frag(Frag<TRANS>& f, const FragAddr<TRANS, BLOCKS>& fa) {
   if constexpr (!TRANS) {
@@ -695,10 +695,10 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   // A hand-ordered software pipeline; __builtin_amdgcn_sched_barrier(0) after every
   // MFMA slot keeps the compiler from regrouping it.  Tile kt is in LDS stage kt % 2 and
   // the pieces of tile kt + 1 are in flight to the other stage on entry.  A k tile is two
-  // 32-wide k steps of 32 MFMAs (4 row blocks x 8 column blocks, row-major).  Every fragment
-  // has one register set and is replaced as soon as its last MFMA of the step has been issued
-  // (an A fragment after its row, a B fragment in row 3), at least eight MFMA slots before it
-  // is needed again:
+  // 32-wide k steps of up to 32 MFMAs (the wavefront's 1..4 row blocks x 8 column blocks,
+  // row-major).  Every fragment has one register set and is replaced as soon as its last MFMA
+  // of the step has been issued (an A fragment after its row, a B fragment in the last row),
+  // eight MFMA slots before it is needed again.  With four row blocks:
   //   step 0: MFMAs | fragments of step 1 as their registers fall free
   //   step 1, row 0: MFMAs
   //   wait for this wavefront's pieces of tile kt + 1 and for its LDS reads; barrier:
