@@ -706,6 +706,20 @@ def test_split_last_round_small_problem(H, F):
         assert torch.equal(getattr(layer, n), getattr(again, n)), n
 
 
+@pytest.mark.parametrize("T", [1, 15, 16, 17, 63, 64, 65, 127, 129, 191, 193, 255, 256, 257, 300, 511])
+def test_ragged_row_tile_every_row_block_count(T):
+    """One expert with T rows: the last row tile holds T mod 256 valid rows, and a wavefront of the grouped
+    GEMM has work in ceil((valid 16-row blocks - its position) / 4) of its four row blocks -- every count
+    from none to four occurs over these T, in all seven products; full check against the oracle."""
+    say("ragged row tile T=%d" % T)
+    w = wl.scaled(wl.CONFIGS[2], T=T, H=128, F=320, E=1, k=1, seed=8300 + T)
+    inp = wl.make_inputs(w, threads=2)
+    layer = run_moe(w, inp)
+    f = f32_inputs(inp)
+    ref = orc.moe_layer(f["logits"], f["x"], f["Wg"], f["Wu"], f["Wd"], w.k, f["dout"])
+    check_layer_full(layer, ref, w.dtype)
+
+
 def test_layer_under_graph_capture():
     """Forward + backward of a layer captured into a HIP graph (no call on the path
     allocates, synchronises or issues a memset) and replayed three times with eager work
