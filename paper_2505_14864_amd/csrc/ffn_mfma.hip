@@ -64,7 +64,6 @@ constexpr int kTableBytes = 64 * 8 * 4;        // the per-expert tile table, kep
 constexpr int kDumpBytes = kWaves * 256;       // where the four-byte loads of the L2 prefetch drop their data
 constexpr int kLdsTotal = kLdsBytes + kTableBytes + kDumpBytes;
 constexpr int kXcds = 8;
-constexpr int kGroupN = 8;                   // column tiles that run side by side in one XCD
 constexpr int kMaxPersistent = 256;          // persistent workgroups per launch (one per compute unit)
 constexpr int kMinSplitKt = 16;              // a k chunk of a split tile is at least this many k tiles long
 constexpr int kMaxSplitTiles = kMaxPersistent / 2;     // tiles of a last round that is worth splitting
@@ -342,11 +341,9 @@ struct Tile {
 };
 
 // The tile list is never materialised.  All tiles of expert 0 come first, then
-// expert 1, ...; inside an expert the column tiles go in groups of kGroupN and,
-// inside a group, consecutive indices walk the column tiles of one row tile before
-// moving to the next row tile, so that the 32 workgroups of an XCD hold a 4 x 8 patch
-// of tiles that share operand tiles in L2.  How the list is dealt to the XCDs
-// depends on what a tile costs:
+// expert 1, ...; inside an expert they go in the order of tile_in_expert() below, chosen
+// so that the 32 consecutive tiles the workgroups of an XCD hold at a time share
+// operand tiles in L2.  How the list is dealt to the XCDs depends on what a tile costs:
 //   * row-segmented products: every tile has the same k range, so each XCD takes one
 //     contiguous eighth of the whole list (fewest distinct weight tiles per L2);
 //   * products that contract over an expert's rows: a tile costs in proportion to
@@ -403,18 +400,78 @@ __device__ __forceinline__ TileTable make_tile_table(int* table, const int32_t* 
   return tb;
 }
 
+// Tile r of an expert with mt row tiles and nt column tiles -> (row tile, column tile): the order
+// in which the list walks an expert's tiles.  32 consecutive tiles run side by side in one XCD
+// and should need few distinct operand tiles, wherever in the expert the run starts (the
+// experts' tile counts are not multiples of 32).
+//   * Many row tiles (`tall`): column tiles in groups of kGroupN, a group walked row tile by row
+//     tile -- a run is 4 row tiles x 8 column tiles, 12 operand tiles, except where it wraps
+//     from a group's last row tiles to the next group's first (once in mt / 4 runs).
+//   * Few row tiles: that wrap would be in every run (20 operand tiles).  The row tiles go in
+//     chunks of about `rows` (nearly equal heights) and a chunk is walked column tile by column
+//     tile, all of its row tiles before the next column tile: a run covers the h row tiles of
+//     the chunk and about 32 / h column tiles, wherever it starts.
+//   * Fewer than 8 column tiles: row tile by row tile over the whole width.
+constexpr int kGroupN = 8;
+__device__ __forceinline__ void tile_in_expert(int mt, int nt, int r, bool tall, int rows, int& mi, int& ni) {
+  mt = max(1, mt);
+  if (nt < kGroupN) {
+    mi = r / nt;
+    ni = r - mi * nt;
+    return;
+  }
+  if (tall) {
+    const int group = r / (mt * kGroupN);
+    const int within = r - group * (mt * kGroupN);
+    const int gn = min(kGroupN, nt - group * kGroupN);
+    mi = within / gn;
+    ni = group * kGroupN + within - mi * gn;
+    return;
+  }
+  const int chunks = max(1, (mt + rows / 2 - 1) / rows);
+  const int h = mt / chunks, taller = mt % chunks;  // the first `taller` chunks have h + 1 rows
+  const int tall_tiles = taller * (h + 1) * nt;
+  int row0, height;
+  if (r < tall_tiles) {
+    const int c = r / ((h + 1) * nt);
+    r -= c * (h + 1) * nt;
+    row0 = c * (h + 1);
+    height = h + 1;
+  } else {
+    r -= tall_tiles;
+    const int c = r / (h * nt);
+    r -= c * h * nt;
+    row0 = taller * (h + 1) + c * h;
+    height = h;
+  }
+  ni = r / height;
+  mi = row0 + r - ni * height;
+}
+// The first order from 13 row tiles on.  Below that, chunks of about 4 row tiles (runs of 4 x 8), or of
+// about 8 (runs of 8 x 4) where operand tiles are small enough to survive in L2 from one run to the
+// next, so that consecutive runs keep 8 tiles instead of 4:
+//   * a short contraction (`short_k`: at most kShortK);
+//   * a token-contracted product whose output has more row tiles than column tiles (dWg, dWu: F x H) --
+//     its k range is an expert's rows -- which takes this order whatever its height (measured: 6 %
+//     faster than 4 x 8 runs that move along F; dWd, H x F, gets the same from the first order).
+constexpr int kTallFrom = 13;
+constexpr int kShortK = 1024;
+constexpr int kMinTouchKt = 16;  // L2 prefetch: only for k ranges of at least that many k tiles
+__device__ __forceinline__ void tile_in_expert(bool dw, bool short_k, int mt, int nt, int r, int& mi, int& ni) {
+  const bool long_rows = dw && mt >= nt;
+  tile_in_expert(mt, nt, r, !long_rows && mt >= kTallFrom, long_rows || short_k ? 8 : 4, mi, ni);
+}
+
 // pos = position in the list
-__device__ __forceinline__ Tile decode_tile(const int* table, const TileTable& tb, int pos, bool dw, int M, int tile_n) {
+__device__ __forceinline__ Tile decode_tile(const int* table, const TileTable& tb, int pos, bool dw, bool short_k, int M, int tile_n) {
   const int lane = threadIdx.x & 63;
   const unsigned long long mask = __ballot(table[kTableStride * lane + 3] > pos);
   const int e = __builtin_ctzll(mask);
   const int* row = table + kTableStride * e;
   const int begin = row[0], end = row[1], mt = row[2];
   const int r = pos + row[4];  // tile index inside expert e
-  const int group = r / (mt * kGroupN);
-  const int within = r - group * (mt * kGroupN);
-  const int gn = min(kGroupN, tb.nt - group * kGroupN);
-  const int mi = within / gn, ni = group * kGroupN + within % gn;
+  int mi, ni;
+  tile_in_expert(dw, short_k, mt, tb.nt, r, mi, ni);
   Tile t;
   t.e = e;
   t.m0 = dw ? mi * BM : begin + mi * BM;
@@ -457,6 +514,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   const TileTable tb = make_tile_table(table, p.seg, p.E, MODE == MODE_DW, p.M, p.N, TILE_N, xcd);
   __syncthreads();
   const int n_end = p.N;
+  const bool short_k = MODE != MODE_DW && p.K <= kShortK;
   // The SIMD favours its older wavefront, which then reaches each k-tile barrier well
   // before the younger one; a higher priority for the younger wavefronts evens that
   // out (measured: a few percent).
@@ -610,51 +668,84 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     constexpr int j = decltype(J)::value;
     load_to_lds<kTileBytes + j * 1024>(q.b, stage + wave_pieces, B_TRANS || WHOLE_K || pb.kpos[j] < q.k_left ? pb.off[j] : kOob);
   };
-  // L2 prefetch.  The workgroups of an XCD that run side by side share operand tiles (a 4 x 8
-  // patch of output tiles: 8 share each A tile, 4 each B tile) and ask for the same lines at
+  // L2 prefetch.  The workgroups of an XCD that run side by side share operand tiles (in a run
+  // of 4 x 8 output tiles, 8 share each A tile and 4 each B tile) and ask for the same lines at
   // about the same time, so every one of them sees the full memory latency on every k tile.
-  // Three k tiles ahead, each line is therefore asked for once: of an A tile this workgroup
-  // touches the 32 lines (rows, or 8 k-rows of 4 lines) that its column-tile index selects
-  // (lanes 0..31 of wavefront 0), of a B tile the 64 lines that its row-tile index selects
-  // (wavefront 1); the other wavefronts issue the same instruction with every lane masked,
-  // which keeps the wait counts alike.  Purely a hint: when the patch is cut short by an
-  // expert's end some lines go untouched, and nothing depends on the data.
-  // Only the products whose operands are both [row][k] are prefetched (gate/up and down: 3 to 9 %
-  // faster on a dense layer).  With a [k][row] operand the same scheme measured slower, whether
-  // that operand's lines were touched too (token-contracted products: -4 to -7 %) or only the
-  // [row][k] one's (dX: -9 %), so those products issue no prefetch at all.
-  constexpr bool TOUCHES = !A_TRANS && !B_TRANS;
+  // Three k tiles ahead, each line is therefore asked for once, by one of the workgroups that
+  // share it -- four bytes per 128-byte line, into a dump area; every wavefront issues one such
+  // instruction per k tile (lanes without a line are masked), which keeps the wait counts
+  // alike.  Purely a hint: nothing depends on the data.
+  // Prefetched: the products whose operands are both [row][k] (gate/up and down: 9 to 12 % faster
+  // when every expert has a multiple of four row tiles) and dX, both operands (Mixtral shape: 6 %
+  // faster; only one of the two operands: 4 to 14 % slower than none).  Not prefetched: dA (+-2 %)
+  // and the token-contracted products (2 to 3 % slower with it).
+  constexpr bool TOUCHES = (!A_TRANS && !B_TRANS) || IS_DX;
   struct Touch {
     uint32_t off;  // this lane's line, as a byte offset from the tile's (row0, k0) element, or kOob
-    bool second;   // gate/up pairing: wavefront 1's lines are in the second matrix
+    bool second;   // gate/up pairing: this wavefront's lines are in the second matrix
   };
-  auto touch_of = [&](const Tile& tt) {
+  // Who shares what is read off the tiles that really run side by side, not assumed: the experts'
+  // tile counts are no multiples of 32, so a run starts anywhere in an expert's tile order and
+  // may span two experts (a fixed partition by tile index left half of the B lines untouched in
+  // such runs, and the prefetch gained nothing on a Mixtral-shaped layer with 3 to 9 row tiles per expert).  Lane j decodes the j-th tile of the
+  // run this workgroup's tile belongs to (`base` = the run's first list position, `n_valid`
+  // tiles, this workgroup's the `me`-th); tiles with the same expert and row tile share the A
+  // tile, tiles with the same expert and column tile the B tile.
+  auto touch_of = [&](const Tile& tt, int kts_of_tile, int base, int n_valid, int me) {
+    if constexpr (!TOUCHES) return Touch{kOob, false};
+    // nothing is touched when the k range (of a phase, for dX) is short (11 k tiles: 4 % slower with the prefetch than without)
+    if (kts_of_tile < kMinTouchKt) return Touch{kOob, MODE == MODE_GATEUP && wave_u >= 6};
     const int tid = tid_now();
     const int lane = tid & 63, wave = tid >> 6;
     const int ni = tt.n0 / TILE_N, mi = (MODE == MODE_DW ? tt.m0 : tt.m0 - tt.k_begin) / BM;
-    const int part = mi & 3;
+    int e_j = -1, mi_j = 0, ni_j = 0;
+    if (lane < n_valid) {
+      const int pos = base + lane;
+      int e = 0;
+      for (int x = 0; x + 1 < p.E; ++x) e += table[kTableStride * x + 3] <= pos ? 1 : 0;
+      const int* row = table + kTableStride * e;
+      e_j = e;
+      tile_in_expert(MODE == MODE_DW, short_k, row[2], tb.nt, pos + row[4], mi_j, ni_j);
+    }
+    const unsigned long long share_a = __ballot(e_j == tt.e && mi_j == mi);
+    const unsigned long long share_b = __ballot(e_j == tt.e && ni_j == ni);
+    const unsigned long long below = (1ull << me) - 1;
+    const int cnt_a = max(1, __builtin_popcountll(share_a)), rank_a = __builtin_popcountll(share_a & below);
+    const int cnt_b = max(1, __builtin_popcountll(share_b)), rank_b = __builtin_popcountll(share_b & below);
     Touch th;
     th.off = kOob;
-    th.second = MODE == MODE_GATEUP && __builtin_amdgcn_readfirstlane(part) >= 2;
-    if (wave == 0 && lane < 32) {
+    th.second = MODE == MODE_GATEUP && __builtin_amdgcn_readfirstlane(wave) >= 6;
+    // The lines of an operand tile go round robin to its `cnt` sharers, this workgroup being the `rank`-th.
+    // Wavefronts 0..3 cover the 256 lines of the A tile, 4..7 those of the B tile (gate/up: 4, 5 the gate
+    // rows, 6, 7 the matching up rows), so the few lines a workgroup touches are spread over all of its
+    // wavefronts (measured: one contiguous block per sharer, issued by one or two wavefronts, is slower --
+    // the down product of that Mixtral-shaped layer by 20 %).  A tile nobody else in the run uses is touched all the same, by its
+    // one user: left out, it runs so much slower than its neighbours that a product of three rounds ends
+    // 20 % later.
+    const int line = (wave & 3) * 64 + lane;
+    if (wave < 4) {
       const int rows_left = tt.m_end - tt.m0;
       if (!A_TRANS) {
-        const int r = (ni & 7) * 32 + lane;
-        if (r < rows_left) th.off = (uint32_t)(gathered ? p.gather[tt.m0 + r] / p.gather_div : r) * lda_b;
+        if (line < rows_left && line % cnt_a == rank_a)
+          th.off = (uint32_t)(gathered ? p.gather[tt.m0 + line] / p.gather_div : line) * lda_b;
+      } else {
+        // [k][row] tile: k-row line / 4, 64-row quarter line % 4 (128 bytes); the record count masks the k range
+        if ((line & 3) * 64 < rows_left && line % cnt_a == rank_a) th.off = (uint32_t)(line >> 2) * lda_b + (line & 3) * 128;
       }
-    } else if (wave == 1) {
+    } else {
       const int cols_left = n_end - tt.n0;
       if (!B_TRANS) {
-        const int lrow = part * 64 + lane;
-        const int row = MODE == MODE_GATEUP ? lrow % 128 : lrow;
-        if (row < cols_left) th.off = (uint32_t)row * ldb_b;
+        const int row = MODE == MODE_GATEUP ? line % 128 : line;
+        if (row < cols_left && line % cnt_b == rank_b) th.off = (uint32_t)row * ldb_b;
+      } else {
+        if ((line & 3) * 64 < cols_left && line % cnt_b == rank_b) th.off = (uint32_t)(line >> 2) * ldb_b + (line & 3) * 128;
       }
     }
     return th;
   };
   const uint32_t lds_dump = lds0 + kLdsBytes + kTableBytes + wave_u * 256;
   auto touch = [&](const KTile& q, const Touch& th) {
-    if constexpr (TOUCHES) touch_to_lds(wave_u == 1 ? q.b : q.a, lds_dump, th.off);
+    if constexpr (TOUCHES) touch_to_lds(wave_u >= 4 ? q.b : q.a, lds_dump, th.off);
   };
   // the k loop's wait for the pieces of the next k tile: the prefetch, if any, is the youngest load and may stay out
   auto wait_pieces = [&]() {
@@ -665,7 +756,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   auto tile_at = [&](int round) {
     const bool parted_t = CAN_SPLIT && round == my_rounds;
     return decode_tile(table, tb, parted_t ? tb.total - tail_tiles + tail_tile : first + round * slots + place(round),
-                       MODE == MODE_DW, p.M, TILE_N);
+                       MODE == MODE_DW, short_k, p.M, TILE_N);
   };
   bool first_in_flight = false;  // the first k tile of the tile about to start is already on its way to stage 0
   for (int round = 0; round < n_rounds; ++round) {
@@ -721,8 +812,6 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   FragAddr<A_TRANS, 4> fra = frag_addr<A_TRANS, 4, 4>(lds0, wave_u >> 1);
   FragAddr<B_TRANS, 8> frb = frag_addr<B_TRANS, 8, 1>(lds0, MODE == MODE_GATEUP ? (wave_u & 1) * 4 : (wave_u & 1) * 8);
   KIter kit = kiter_at(t, kr, kt_lo, second_b);  // the k tiles to load, in order
-  const Touch th = touch_of(t);
-  KIter kit_touch = kiter_at(t, kr, kt_lo + 2, th.second);  // the k tiles to prefetch, in order
   // A fragment of row block I / B fragment of column block J for k step H
   // (the stage read is the one fra / frb point into)
   auto read_a = [&](auto I, auto H) {
@@ -741,6 +830,14 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   const std::integral_constant<int, 1> c1;
   const std::integral_constant<int, 2> c2_;
 
+  // What this workgroup prefetches is worked out with the first two k tiles on their way, where it costs
+  // no time -- unless that takes a global load itself (the gather indices), which would wait for them.
+  auto touch_now = [&]() {
+    return parted ? touch_of(t, min(kt_hi - kt_lo, kr.kt_per_phase), tb.total - tail_tiles + (xcd / split) * slots, min(slots, tail_tiles - (xcd / split) * slots), slot)
+                  : touch_of(t, min(kt_hi - kt_lo, kr.kt_per_phase), first + round * slots, min(slots, mine - round * slots), place(round));
+  };
+  Touch th{kOob, false};
+  if (gathered) th = touch_now();
   {
     const KTile q0 = knext(kit);
     if (!first_in_flight) {
@@ -753,6 +850,8 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     static_for<kPieces>([&](auto J) { dma_a(pa, q1, lds0 + kStageBytes, J); });
     static_for<kPieces>([&](auto J) { dma_b(pb, q1, lds0 + kStageBytes, J); });
   }
+  if (!gathered) th = touch_now();
+  KIter kit_touch = kiter_at(t, kr, kt_lo + 2, th.second);  // the k tiles to prefetch, in order
   if constexpr (TOUCHES) touch(knext(kit_touch), th);
   wait_loads_but<2 * kPieces + (TOUCHES ? 1 : 0)>();  // the first tile has landed
   wg_barrier();
