@@ -344,13 +344,12 @@ struct Tile {
 // expert 1, ...; inside an expert they go in the order of tile_in_expert() below, chosen
 // so that the 32 consecutive tiles the workgroups of an XCD hold at a time share
 // operand tiles in L2.  How the list is dealt to the XCDs depends on what a tile costs:
-//   * row-segmented products: every tile has the same k range, so each XCD takes one
-//     contiguous eighth of the whole list (fewest distinct weight tiles per L2);
+//   * row-segmented products: every tile has the same k range; each XCD takes one
+//     contiguous eighth of the whole list, or, with several experts (whose tiles cost
+//     what their ragged last row tiles make them cost), every eighth run of 32 tiles;
 //   * products that contract over an expert's rows: a tile costs in proportion to
 //     the expert's row count, so each XCD takes an eighth of EVERY expert's tiles
 //     (whole experts per XCD would leave the most loaded one working alone).
-// Either way an XCD's share of an expert is one contiguous run, and the XCD walks
-// its runs expert by expert as one flat list.
 struct TileTable {
   int nt;     // column tiles (same for all experts)
   int total;  // tiles in the list decode_tile() indexes: the whole list for the row-segmented
@@ -521,7 +520,8 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   if (threadIdx.x >= kMfmaThreads / 2) __builtin_amdgcn_s_setprio(1);
   // Who runs what.  Products that contract over an expert's rows: the XCD's own list,
   // one tile per workgroup and round.  Row-segmented products: XCD x takes the x-th
-  // contiguous eighth of the whole list.  If the last round of the grid would leave at
+  // contiguous eighth of the whole list (one expert) or every eighth run of 32 tiles
+  // (several experts; below).  If the last round of the grid would leave at
   // least half of the XCDs idle (`patches` XCD-sized patches of tiles, 2 * patches <= 8),
   // those last tiles are taken out of the eighths and each patch is run by `split` XCDs
   // at once, every one on its own chunk of the k range: a patch keeps the operand
@@ -550,8 +550,19 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   // multiple of four row tiles (a multiple of eight places otherwise: hence a step that is not), over the
   // workgroups, whose tile counts are fixed.
   auto place = [&](int round) { return (slot + 5 * round) % slots; };
-  const int whole_rounds = mine / slots;
-  const int my_rounds = whole_rounds + (place(whole_rounds) < mine - whole_rounds * slots ? 1 : 0);
+  // Row-segmented products over several experts: the runs of `slots` consecutive tiles go round robin to
+  // the XCDs instead (run g to XCD g % 8).  A contiguous eighth holds whole experts, and an expert's tiles
+  // cost what its ragged last row tile makes them cost: on a Mixtral-shaped layer the XCDs finished up to
+  // 7 % apart.  Dealt round robin every XCD gets the same mix (that layer: gate/up -2 %, down -6 %, dA
+  // -5 %).  A single expert keeps the eighths: there the XCDs that walk the same rows side by side share
+  // them through the Infinity Cache (dense dA: 12 % slower round robin).
+  const bool rr = MODE != MODE_DW && p.E > 1;
+  const int main_tiles = rr ? tb.total - tail_tiles : mine;
+  auto run_base = [&](int round) { return rr ? (round * kXcds + xcd) * slots : first + round * slots; };
+  auto run_len = [&](int round) { return max(0, min(slots, (rr ? main_tiles : first + mine) - run_base(round))); };
+  const int runs = (main_tiles + slots - 1) / slots;
+  const int xcd_rounds = rr ? (runs > xcd ? (runs - xcd + kXcds - 1) / kXcds : 0) : (mine + slots - 1) / slots;
+  const int my_rounds = xcd_rounds > 0 && place(xcd_rounds - 1) >= run_len(xcd_rounds - 1) ? xcd_rounds - 1 : xcd_rounds;
   const int tail_tile = (xcd / split) * slots + slot;  // index among the split tiles
   const bool has_part = split > 1 && tail_tile < tail_tiles;
   if (CAN_SPLIT && p.partial != nullptr && blockIdx.x == 0 && threadIdx.x == 0) {
@@ -755,7 +766,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   const int n_rounds = my_rounds + (has_part ? 1 : 0);
   auto tile_at = [&](int round) {
     const bool parted_t = CAN_SPLIT && round == my_rounds;
-    return decode_tile(table, tb, parted_t ? tb.total - tail_tiles + tail_tile : first + round * slots + place(round),
+    return decode_tile(table, tb, parted_t ? tb.total - tail_tiles + tail_tile : run_base(round) + place(round),
                        MODE == MODE_DW, short_k, p.M, TILE_N);
   };
   bool first_in_flight = false;  // the first k tile of the tile about to start is already on its way to stage 0
@@ -834,7 +845,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
   // no time -- unless that takes a global load itself (the gather indices), which would wait for them.
   auto touch_now = [&]() {
     return parted ? touch_of(t, min(kt_hi - kt_lo, kr.kt_per_phase), tb.total - tail_tiles + (xcd / split) * slots, min(slots, tail_tiles - (xcd / split) * slots), slot)
-                  : touch_of(t, min(kt_hi - kt_lo, kr.kt_per_phase), first + round * slots, min(slots, mine - round * slots), place(round));
+                  : touch_of(t, min(kt_hi - kt_lo, kr.kt_per_phase), run_base(round), run_len(round), place(round));
   };
   Touch th{kOob, false};
   if (gathered) th = touch_now();
