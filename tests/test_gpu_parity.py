@@ -720,6 +720,30 @@ def test_ragged_row_tile_every_row_block_count(T):
     check_layer_full(layer, ref, w.dtype)
 
 
+@pytest.mark.parametrize("counts", [(100, 300, 700, 1300, 1800, 3400), (3329, 257, 0, 1, 2049, 1537)])
+def test_tile_order_mixed_row_tile_counts(counts):
+    """Experts with 0, 1, 2, 3, 6, 7, 8, 9 and 14 row tiles in one layer whose products have 8 or 16 column
+    tiles: the grouped GEMM walks an expert's tiles in one chunk, in several chunks of about four (or eight) row
+    tiles, or in column groups, depending on its row-tile count, deals runs of 32 tiles round robin to the XCDs,
+    and every workgroup works out from the run it is in which operand lines it prefetches; a tile left out or
+    done twice by any of that shows in the full check against the oracle (top-1 routing with exactly these
+    rows per expert, tokens in random order)."""
+    say("tile order counts=%s" % (counts,))
+    T, E = sum(counts), len(counts)
+    w = wl.scaled(wl.CONFIGS[2], T=T, H=2048, F=2048, E=E, k=1, seed=8400 + counts[0])
+    inp = wl.make_inputs(w, threads=4)
+    rng = np.random.default_rng(w.seed)
+    expert_of = rng.permutation(np.repeat(np.arange(E), counts))
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    logits[np.arange(T), expert_of] += 20.0
+    inp["logits"] = logits
+    layer = run_moe(w, inp)
+    assert to_host(layer.seg_offsets).tolist() == np.concatenate([[0], np.cumsum(counts)]).tolist()
+    f = f32_inputs(inp)
+    ref = orc.moe_layer(f["logits"], f["x"], f["Wg"], f["Wu"], f["Wd"], w.k, f["dout"])
+    check_layer_full(layer, ref, w.dtype)
+
+
 def test_layer_under_graph_capture():
     """Forward + backward of a layer captured into a HIP graph (no call on the path
     allocates, synchronises or issues a memset) and replayed three times with eager work
