@@ -177,6 +177,8 @@ def main():
                 x = layer.forward_folded(x, *Ws[i], out=layer.out)
             else:
                 x = layer.forward(x, *Ws[i])
+            # the rows are permuted: the load is known, and its copy to the host can run behind the forward pass
+            layer.load_begin()
         g = dev["dout"]
         for i in range(L - 1, -1, -1):
             if a.folded_combine:
@@ -194,7 +196,7 @@ def main():
                 layers[i].route_bwd(dev["scores"])
         rows, loads = 0, []
         for layer in layers:
-            counts, load = layer.load()  # device -> host, synchronises the stream
+            counts, load = layer.load_end()  # waits for this layer's copy only, which finished long ago
             rows += sum(counts)
             loads.append(load if L > 1 else [c * 18.0 * w.H * w.F for c in counts])
         per_task = loads if L > 1 else loads[0]

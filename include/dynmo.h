@@ -13,7 +13,8 @@
  *     comes from the caller's workspace (size from dynmo_*_workspace_bytes).
  *   - outputs are overwritten, never accumulated into.
  *   - `stream` is a hipStream_t (NULL = the default stream).  Calls enqueue work
- *     and return; only dynmo_layer_load synchronises the stream.
+ *     and return; only dynmo_layer_load synchronises the stream (dynmo_layer_load_begin /
+ *     _end are the same export without that).
  *   - activation, weight and gradient tensors must be 16-byte aligned (rows move in
  *     16-byte pieces); a misaligned one gives DYNMO_EINVAL.  Workspaces need no alignment
  *     (the *_workspace_bytes values include the slack the library needs to align them).
@@ -257,6 +258,18 @@ int32_t dynmo_combine_bwd(const dynmo_desc* d, const void* dout, const void* y_p
  * are HOST pointers. */
 int32_t dynmo_layer_load(const dynmo_desc* d, const int32_t* seg_offsets, double cost_per_row,
                          int32_t* counts_host, double* load_host, void* stream);
+
+/* The same export in two halves, for a caller that must not stall the stream: the segment
+ * offsets are final once dynmo_permute has run, long before the layer's backward pass ends.
+ * dynmo_layer_load_begin enqueues the copy of seg_offsets [E+1] into seg_host and returns
+ * without waiting; seg_host is a HOST pointer to E+1 ints of PINNED memory (hipHostMalloc, a
+ * pinned tensor) that the caller owns and keeps alive and unread until it knows the copy has
+ * completed (an event it recorded behind this call, or any later synchronisation of `stream`).
+ * dynmo_layer_load_end then turns seg_host into counts_host [E] and *load_host exactly as
+ * dynmo_layer_load does; it is host arithmetic only and makes no GPU call. */
+int32_t dynmo_layer_load_begin(const dynmo_desc* d, const int32_t* seg_offsets, int32_t* seg_host, void* stream);
+int32_t dynmo_layer_load_end(const dynmo_desc* d, const int32_t* seg_host, double cost_per_row,
+                             int32_t* counts_host, double* load_host);
 
 /* Partition balancer (Sec. 3.3, Sec. 5): the contiguous split of loads[L] into S
  * stages that minimises the largest stage load (the min-max objective of Sec. 2),

@@ -65,6 +65,8 @@ SIGNATURES = {
     "dynmo_combine": (_I, [_D, _P, _P, _P, _P, _P, _P]),
     "dynmo_combine_bwd": (_I, [_D, _P, _P, _P, _P, _P, _P, _P]),
     "dynmo_layer_load": (_I, [_D, _P, C.c_double, C.POINTER(C.c_int32), C.POINTER(C.c_double), _P]),
+    "dynmo_layer_load_begin": (_I, [_D, _P, _P, _P]),
+    "dynmo_layer_load_end": (_I, [_D, _P, C.c_double, C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
     "dynmo_partition": (_I, [C.POINTER(C.c_double), _I, _I, C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
     "dynmo_partition_shadow": (_I, [C.POINTER(C.c_double), C.POINTER(C.c_int32), _I, _I, C.POINTER(C.c_int32),
                                     C.POINTER(C.c_double), C.POINTER(C.c_int32)]),
@@ -114,6 +116,12 @@ def _ptr(t):
         return None
     if not t.is_cuda or not t.is_contiguous():
         raise ValueError("expected a contiguous GPU tensor")
+    return t.data_ptr()
+
+
+def _pinned_ptr(t, n):
+    if t.is_cuda or not t.is_pinned() or not t.is_contiguous() or t.dtype != torch.int32 or t.numel() < n:
+        raise ValueError("expected a contiguous pinned int32 host tensor of at least %d elements" % n)
     return t.data_ptr()
 
 
@@ -261,6 +269,21 @@ def dynmo_layer_load(d, seg_offsets, cost_per_row, stream=None):
     load = C.c_double()
     _check("dynmo_layer_load", lib().dynmo_layer_load(C.byref(d), _ptr(seg_offsets), float(cost_per_row), counts,
                                                       C.byref(load), _stream(stream)))
+    return list(counts), load.value
+
+
+def dynmo_layer_load_begin(d, seg_offsets, seg_host, stream=None):
+    """Enqueues the copy of seg_offsets into seg_host (a pinned int32 host tensor of E+1 elements); no wait."""
+    _check("dynmo_layer_load_begin", lib().dynmo_layer_load_begin(C.byref(d), _ptr(seg_offsets), _pinned_ptr(seg_host, d.E + 1),
+                                                                  _stream(stream)))
+
+
+def dynmo_layer_load_end(d, seg_host, cost_per_row):
+    """Returns (counts list[E], load float) from seg_host once its copy has completed.  No GPU call."""
+    counts = (C.c_int32 * d.E)()
+    load = C.c_double()
+    _check("dynmo_layer_load_end", lib().dynmo_layer_load_end(C.byref(d), _pinned_ptr(seg_host, d.E + 1), float(cost_per_row), counts,
+                                                              C.byref(load)))
     return list(counts), load.value
 
 

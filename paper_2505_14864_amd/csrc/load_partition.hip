@@ -25,6 +25,30 @@ extern "C" int32_t dynmo_layer_load(const dynmo_desc* d, const int32_t* seg_offs
   return DYNMO_OK;
 }
 
+extern "C" int32_t dynmo_layer_load_begin(const dynmo_desc* d, const int32_t* seg_offsets, int32_t* seg_host,
+                                          void* stream) {
+  int32_t rc = check_desc(d);
+  if (rc) return rc;
+  if (!seg_offsets || !seg_host) return DYNMO_EINVAL;
+  DYNMO_HIP_TRY(hipMemcpyAsync(seg_host, seg_offsets, sizeof(int32_t) * (d->E + 1), hipMemcpyDeviceToHost,
+                               (hipStream_t)stream));
+  return DYNMO_OK;
+}
+
+extern "C" int32_t dynmo_layer_load_end(const dynmo_desc* d, const int32_t* seg_host, double cost_per_row,
+                                        int32_t* counts_host, double* load_host) {
+  int32_t rc = check_desc(d);
+  if (rc) return rc;
+  if (!seg_host || !counts_host || !load_host) return DYNMO_EINVAL;
+  double rows = 0.0;
+  for (int e = 0; e < d->E; ++e) {
+    counts_host[e] = seg_host[e + 1] - seg_host[e];
+    rows += (double)counts_host[e];
+  }
+  *load_host = rows * cost_per_row;
+  return DYNMO_OK;
+}
+
 namespace {
 
 // Stage sums are differences of one running prefix sum, so that every candidate

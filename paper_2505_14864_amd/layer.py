@@ -60,6 +60,9 @@ class RoutedFFNLayer:
         self.out = torch.empty((T, H), **act)
         self.ws_permute = torch.empty((max(1, B.dynmo_permute_workspace_bytes(self.d)),), dtype=torch.uint8, device=dev)
         self.ws_fwd = torch.empty((B.dynmo_grouped_ffn_fwd_workspace_bytes(self.d),), dtype=torch.uint8, device=dev)
+        # the load export's landing place on the host (pinned, so that the copy does not stall the stream)
+        self._seg_host = torch.empty(E + 1, dtype=torch.int32, pin_memory=True)
+        self._seg_event = torch.cuda.Event()
         self._bwd_ready = False
         self._dev = dev
 
@@ -163,3 +166,15 @@ class RoutedFFNLayer:
     def load(self, cost_per_row=None):
         c = 18.0 * self.H * self.F if cost_per_row is None else cost_per_row
         return B.dynmo_layer_load(self.d, self.seg_offsets, c)
+
+    def load_begin(self):
+        """The load export without a stall: enqueues the copy of the segment offsets (final once the rows
+        are permuted) into pinned host memory and records an event behind it; load_end() waits for that
+        event only, not for whatever the stream was given since."""
+        B.dynmo_layer_load_begin(self.d, self.seg_offsets, self._seg_host)
+        self._seg_event.record()
+
+    def load_end(self, cost_per_row=None):
+        c = 18.0 * self.H * self.F if cost_per_row is None else cost_per_row
+        self._seg_event.synchronize()
+        return B.dynmo_layer_load_end(self.d, self._seg_host, c)

@@ -744,6 +744,29 @@ def test_tile_order_mixed_row_tile_counts(counts):
     check_layer_full(layer, ref, w.dtype)
 
 
+def test_layer_load_in_two_halves():
+    """dynmo_layer_load_begin / _end (copy enqueued behind the permutation, read after an event) give the
+    counts and the load of the synchronising dynmo_layer_load, also with more work queued behind the copy."""
+    say("layer load in two halves")
+    w = wl.scaled(wl.CONFIGS[2], T=700, H=128, F=256, E=5, k=2, seed=8600)
+    inp = wl.make_inputs(w, threads=2)
+    dev = {n: to_device(a) for n, a in inp.items()}
+    layer = RoutedFFNLayer(w.T, w.H, w.F, w.E, w.k, w.dtype, "moe")
+    layer.route_topk(dev["logits"])
+    layer.forward(dev["x"], dev["Wg"], dev["Wu"], dev["Wd"])
+    layer.load_begin()
+    layer.backward(dev["dout"], dev["Wg"], dev["Wu"], dev["Wd"])  # queued behind the copy
+    counts, load = layer.load_end()
+    ref_counts, ref_load = layer.load()
+    assert counts == ref_counts and load == ref_load
+    assert sum(counts) == w.T * w.k
+    f = f32_inputs(inp)
+    ref_idx, _ = orc.route_topk(f["logits"], w.k)
+    assert counts == np.bincount(ref_idx.ravel(), minlength=w.E).tolist()
+    with pytest.raises(ValueError):  # the landing place must be pinned host memory
+        B.dynmo_layer_load_begin(layer.d, layer.seg_offsets, torch.empty(w.E + 1, dtype=torch.int32))
+
+
 def test_layer_under_graph_capture():
     """Forward + backward of a layer captured into a HIP graph (no call on the path
     allocates, synchronises or issues a memset) and replayed three times with eager work
