@@ -491,7 +491,19 @@ __device__ __forceinline__ void static_for(F&& f) {
   static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
-__device__ __forceinline__ float silu_mul(float g, float u) { return g * sigmoidf_(g) * u; }
+// The logistic function for results that are rounded to bf16: the hardware reciprocal (1 ulp) instead of a
+// correctly rounded division, which is ten instructions per element in epilogues that are bound by their
+// vector arithmetic.
+__device__ __forceinline__ float sigmoid_bf16(float z) { return __builtin_amdgcn_rcpf(1.0f + __expf(-z)); }
+__device__ __forceinline__ float silu_mul(float g, float u) { return g * sigmoid_bf16(g) * u; }
+// swiglu_bwd() of ffn.h with that reciprocal
+__device__ __forceinline__ void swiglu_bwd_bf16(float dA, float g, float u, float* a, float* dg, float* du) {
+  const float s = sigmoid_bf16(g);
+  const float gs = g * s;
+  *a = gs * u;
+  *dg = dA * u * (s * (1.f + g * (1.f - s)));
+  *du = dA * gs;
+}
 
 // WHOLE_K: the contraction length is a multiple of the k tile, so the [row][k] operands need no
 // per-lane k mask (the [k][row] operands never do: their k range is the buffer's record count).
@@ -1097,7 +1109,7 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
             unpack16<bf16_t>(*(const u32x4*)(Gs + o), g);
             unpack16<bf16_t>(*(const u32x4*)(Us + o), u);
 #pragma unroll
-            for (int q = 0; q < 8; ++q) swiglu_bwd(v[q], g[q], u[q], &a_[q], &dg[q], &du[q]);
+            for (int q = 0; q < 8; ++q) swiglu_bwd_bf16(v[q], g[q], u[q], &a_[q], &dg[q], &du[q]);
             *(u32x4*)(C0 + o) = pack16<bf16_t>(dg);
             *(u32x4*)(C1 + o) = pack16<bf16_t>(du);
             *(u32x4*)(C2 + o) = pack16<bf16_t>(a_);
