@@ -740,11 +740,10 @@ __global__ __launch_bounds__(kMfmaThreads, 1) void ffn_mfma_kernel(const GemmPar
     th.second = MODE == MODE_GATEUP && __builtin_amdgcn_readfirstlane(wave) >= 6;
     // The lines of an operand tile go round robin to its `cnt` sharers, this workgroup being the `rank`-th.
     // Wavefronts 0..3 cover the 256 lines of the A tile, 4..7 those of the B tile (gate/up: 4, 5 the gate
-    // rows, 6, 7 the matching up rows), so the few lines a workgroup touches are spread over all of its
-    // wavefronts (measured: one contiguous block per sharer, issued by one or two wavefronts, is slower --
-    // the down product of that Mixtral-shaped layer by 20 %).  A tile nobody else in the run uses is touched all the same, by its
-    // one user: left out, it runs so much slower than its neighbours that a product of three rounds ends
-    // 20 % later.
+    // rows, 6, 7 the matching up rows).  (One contiguous block of lines per sharer instead measured the same,
+    // +-1 %.)  A tile nobody else in the run uses is touched all the same, by its one user: left out, it runs
+    // so much slower than its neighbours that a product of three rounds -- down on a Mixtral-shaped layer, where
+    // ten of 576 tiles are in that position -- ends 20 % later.
     const int line = (wave & 3) * 64 + lane;
     if (wave < 4) {
       const int rows_left = tt.m_end - tt.m0;
